@@ -1,0 +1,249 @@
+"""ctypes front end of the C oracle (``nmf_mu_oracle.c``) plus two tiny
+pure-Python routines used only to cross-check it on very small shapes.
+
+TEST INFRASTRUCTURE ONLY.  Imported by ``tests/``, by the smoke check and by
+the ``cpu_baseline`` leg of the benchmark; never by the GPU library or its
+Python binding.  All arithmetic is IEEE double.  The iteration order is the
+one of the paper's Algorithm 3 run on a single unit: H update, then W update
+with the new H.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nmf_mu_oracle.c")
+_LIB = os.path.join(_HERE, "libnmf_mu_oracle.so")
+
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the C oracle with gcc (OpenMP, baseline x86-64) if needed."""
+    stale = (not os.path.exists(_LIB)) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC)
+    if force or stale:
+        subprocess.check_call(
+            ["gcc", "-O3", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+             "-o", _LIB, _SRC, "-lm"])
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    build()
+    lib = ctypes.CDLL(_LIB)
+    i64, i32, f64 = ctypes.c_int64, ctypes.c_int32, ctypes.c_double
+    vp = ctypes.c_void_p
+    lib.oracle_num_threads.restype = ctypes.c_int
+    lib.oracle_get_mac_count.restype = ctypes.c_longlong
+    lib.oracle_gram_w.argtypes = [vp, i64, i32, vp]
+    lib.oracle_gram_h.argtypes = [vp, i32, i64, vp]
+    lib.oracle_wta_dense.argtypes = [vp, i64, i64, vp, i32, vp]
+    lib.oracle_aht_dense.argtypes = [vp, i64, i64, vp, i32, vp]
+    lib.oracle_wta_csr.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp]
+    lib.oracle_aht_csr.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp]
+    lib.oracle_h_update.argtypes = [vp, vp, vp, i32, i64, f64]
+    lib.oracle_w_update.argtypes = [vp, vp, vp, i64, i32, f64]
+    lib.oracle_mu_dense.argtypes = [vp, i64, i64, i32, vp, vp, i32, f64]
+    lib.oracle_mu_dense.restype = ctypes.c_int
+    lib.oracle_mu_csr.argtypes = [vp, vp, vp, i64, i64, i32, vp, vp, i32, f64]
+    lib.oracle_mu_csr.restype = ctypes.c_int
+    lib.oracle_h_step_dense.argtypes = [vp, i64, i64, i32, vp, vp, f64]
+    lib.oracle_h_step_dense.restype = ctypes.c_int
+    lib.oracle_w_step_dense.argtypes = [vp, i64, i64, i32, vp, vp, f64]
+    lib.oracle_w_step_dense.restype = ctypes.c_int
+    lib.oracle_residual_dense.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.oracle_residual_dense.restype = f64
+    _lib = lib
+    return lib
+
+
+def _p(a: np.ndarray):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a, shape=None):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if shape is not None:
+        assert a.shape == shape, (a.shape, shape)
+    return a
+
+
+def _f64(a, shape=None):
+    a = np.array(a, dtype=np.float64, order="C", copy=True)
+    if shape is not None:
+        assert a.shape == shape, (a.shape, shape)
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().oracle_num_threads())
+
+
+def reset_mac_count() -> None:
+    _load().oracle_reset_mac_count()
+
+
+def mac_count() -> int:
+    return int(_load().oracle_get_mac_count())
+
+
+# ---- single products (Algorithm 3, one line each) -------------------------
+
+def gram_w(W):
+    W = _f64(W)
+    m, k = W.shape
+    G = np.empty((k, k))
+    _load().oracle_gram_w(_p(W), m, k, _p(G))
+    return G
+
+
+def gram_h(H):
+    H = _f64(H)
+    k, n = H.shape
+    G = np.empty((k, k))
+    _load().oracle_gram_h(_p(H), k, n, _p(G))
+    return G
+
+
+def wta_dense(A, W):
+    A = _f32(A)
+    W = _f64(W)
+    m, n = A.shape
+    k = W.shape[1]
+    assert W.shape[0] == m
+    P = np.empty((k, n))
+    _load().oracle_wta_dense(_p(A), m, n, _p(W), k, _p(P))
+    return P
+
+
+def aht_dense(A, H):
+    A = _f32(A)
+    H = _f64(H)
+    m, n = A.shape
+    k = H.shape[0]
+    assert H.shape[1] == n
+    Q = np.empty((m, k))
+    _load().oracle_aht_dense(_p(A), m, n, _p(H), k, _p(Q))
+    return Q
+
+
+def _csr(rowptr, colidx, vals):
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int64)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    assert rowptr[0] == 0 and rowptr[-1] == colidx.size == vals.size
+    return rowptr, colidx, vals
+
+
+def wta_csr(rowptr, colidx, vals, n, W):
+    rowptr, colidx, vals = _csr(rowptr, colidx, vals)
+    W = _f64(W)
+    m, k = W.shape
+    assert rowptr.size == m + 1
+    P = np.empty((k, n))
+    _load().oracle_wta_csr(_p(rowptr), _p(colidx), _p(vals), m, n, _p(W), k, _p(P))
+    return P
+
+
+def aht_csr(rowptr, colidx, vals, H):
+    rowptr, colidx, vals = _csr(rowptr, colidx, vals)
+    H = _f64(H)
+    k, n = H.shape
+    m = rowptr.size - 1
+    Q = np.empty((m, k))
+    _load().oracle_aht_csr(_p(rowptr), _p(colidx), _p(vals), m, n, _p(H), k, _p(Q))
+    return Q
+
+
+def h_update(H, P, G, eps):
+    H = _f64(H)
+    k, n = H.shape
+    P = _f64(P, (k, n))
+    G = _f64(G, (k, k))
+    _load().oracle_h_update(_p(H), _p(P), _p(G), k, n, float(eps))
+    return H
+
+
+def w_update(W, Q, G, eps):
+    W = _f64(W)
+    m, k = W.shape
+    Q = _f64(Q, (m, k))
+    G = _f64(G, (k, k))
+    _load().oracle_w_update(_p(W), _p(Q), _p(G), m, k, float(eps))
+    return W
+
+
+# ---- whole iterations ------------------------------------------------------
+
+def mu_dense(A, W0, H0, iters, eps):
+    """`iters` MU iterations (H then W) on dense A; returns (W, H) in double."""
+    A = _f32(A)
+    m, n = A.shape
+    W = _f64(W0)
+    H = _f64(H0)
+    k = W.shape[1]
+    assert W.shape == (m, k) and H.shape == (k, n)
+    rc = _load().oracle_mu_dense(_p(A), m, n, k, _p(W), _p(H), int(iters), float(eps))
+    if rc != 0:
+        raise MemoryError("oracle_mu_dense")
+    return W, H
+
+
+def mu_csr(rowptr, colidx, vals, m, n, W0, H0, iters, eps):
+    rowptr, colidx, vals = _csr(rowptr, colidx, vals)
+    W = _f64(W0)
+    H = _f64(H0)
+    k = W.shape[1]
+    assert rowptr.size == m + 1 and W.shape == (m, k) and H.shape == (k, n)
+    rc = _load().oracle_mu_csr(_p(rowptr), _p(colidx), _p(vals), m, n, k,
+                               _p(W), _p(H), int(iters), float(eps))
+    if rc != 0:
+        raise MemoryError("oracle_mu_csr")
+    return W, H
+
+
+def h_step_dense(A, W, H, eps):
+    A = _f32(A)
+    m, n = A.shape
+    W = _f64(W)
+    H = _f64(H)
+    _load().oracle_h_step_dense(_p(A), m, n, W.shape[1], _p(W), _p(H), float(eps))
+    return W, H
+
+
+def w_step_dense(A, W, H, eps):
+    A = _f32(A)
+    m, n = A.shape
+    W = _f64(W)
+    H = _f64(H)
+    _load().oracle_w_step_dense(_p(A), m, n, W.shape[1], _p(W), _p(H), float(eps))
+    return W, H
+
+
+def residual_dense(A, W, H) -> float:
+    """||A - W H||_F (paper, section 2.1)."""
+    A = _f32(A)
+    m, n = A.shape
+    W = _f64(W)
+    H = _f64(H)
+    return float(_load().oracle_residual_dense(_p(A), m, n, W.shape[1], _p(W), _p(H)))
+
+
+def mu_ensemble(As, W0s, H0s, iters, eps):
+    """Independent runs, one after another (NMFk-style ensemble)."""
+    return [mu_dense(A, W0, H0, iters, eps) for A, W0, H0 in zip(As, W0s, H0s)]
+
+
+def rel_fro(X, Xref) -> float:
+    """||X - Xref||_F / ||Xref||_F in double; the parity metric."""
+    X = np.asarray(X, dtype=np.float64)
+    Xref = np.asarray(Xref, dtype=np.float64)
+    den = np.linalg.norm(Xref)
+    return float(np.linalg.norm(X - Xref) / den) if den > 0 else float(np.linalg.norm(X))
