@@ -1,0 +1,166 @@
+/*
+ * nmfmu.h -- C ABI of the MI355X (gfx950) multiplicative-update NMF library.
+ *
+ * The library runs the Frobenius-norm multiplicative-update (MU) iteration for
+ * A ~= W H with W, H >= 0 (paper, section 2.1 and Algorithm 1) in the order of
+ * the paper's row-partition algorithm (Algorithm 3) on a single device:
+ *
+ *     H <- H * (W^T A) / ((W^T W) H + eps)          H update, old H on the right
+ *     W <- W * (A H^T) / (W (H H^T) + eps)          W update, uses the NEW H
+ *
+ * eps is added once, to the finished denominator.  Arithmetic is IEEE single
+ * precision throughout (products on the matrix cores with fp32 operands and
+ * fp32 accumulation).
+ *
+ * Conventions shared by every entry point
+ *   - All matrices are row-major and contiguous: A is m x n (leading dimension
+ *     n), W is m x k (ld k), H is k x n (ld n).  Base pointers must be 4-byte
+ *     aligned; the fast paths need 16-byte aligned A and H and n % 4 == 0,
+ *     anything else takes a slower, equally correct path.
+ *   - "device" pointers are HIP device memory of the current device; "host"
+ *     pointers are host memory.  The caller owns every buffer; the library
+ *     keeps no reference to them after the call's work has finished.
+ *   - W and H are read and overwritten in place; after the enqueued work has
+ *     completed they hold the factors after `iters` iterations.
+ *   - `stream` is a hipStream_t passed as void*; NULL means the null stream.
+ *     nmf_mu_dense / nmf_mu_csr / nmf_mu_dense_batched only enqueue work and
+ *     return; nmf_mu_ooc also drives internal copy streams and may block the
+ *     calling thread while it throttles copies, but does not synchronise the
+ *     device; on return all of its work is ordered before anything enqueued
+ *     on `stream` afterwards.
+ *   - Scratch memory (partial sums, Gram matrices) comes from a per-process
+ *     workspace that the library allocates on first use and grows on demand,
+ *     or from a caller-provided block (nmf_mu_set_workspace).  Calls that run
+ *     concurrently on one device share it and therefore race: serialise them.
+ *   - Every function returns a status code and never throws, exits or prints.
+ *     Entries of A, W, H are not inspected: negative or non-finite input gives
+ *     an undefined (but non-faulting) result.  iters == 0 is a successful
+ *     no-op.  Supported rank: 1 <= k <= NMF_MU_MAX_K.
+ */
+#ifndef NMFMU_H
+#define NMFMU_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    NMF_OK = 0,
+    NMF_EINVAL = 1,       /* null pointer, non-positive size, bad eps/iters/batch */
+    NMF_ENOMEM = 2,       /* workspace or staging buffers do not fit */
+    NMF_EHIP = 3,         /* a HIP runtime call failed; see nmf_last_error() */
+    NMF_EUNSUPPORTED = 4  /* k > NMF_MU_MAX_K */
+};
+
+#define NMF_MU_MAX_K 64
+
+/* Static, human-readable name of a status code. */
+const char *nmf_status_string(int status);
+
+/* Detail of the last failure on the calling thread (thread-local storage,
+ * valid until the next failing call on that thread); "" if none. */
+const char *nmf_last_error(void);
+
+/*
+ * Resident dense MU (Algorithm 3 on one unit).
+ *   A      device, m x n, read-only
+ *   W, H   device, in/out
+ *   iters  >= 0;  eps >= 0 and finite
+ * Asynchronous on `stream`.
+ */
+int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
+                 float *W, float *H, int32_t iters, float eps, void *stream);
+
+/*
+ * Resident sparse MU: the same iteration with A given in CSR (section 2.3
+ * names the three CSR arrays: values, column indices, row pointers).
+ *   rowptr  device, int64[m + 1], non-decreasing, rowptr[0] = 0, rowptr[m] = nnz
+ *   colidx  device, int32[nnz], each in [0, n); order within a row is free and
+ *           repeated (row, column) pairs add up
+ *   vals    device, float[nnz]
+ * The CSR arrays are read-only and are not reordered or copied; the only
+ * derived structure is a transposed copy of H (n x k) in the workspace.
+ * Sums over stored entries use fp32 atomics for W^T A, so low-order bits may
+ * differ from run to run.  Asynchronous on `stream`.
+ */
+int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+               int64_t m, int64_t n, int64_t nnz, int32_t k,
+               float *W, float *H, int32_t iters, float eps, void *stream);
+
+/*
+ * Out-of-memory dense MU: A stays in host memory and is streamed to the device
+ * in batches of `batch_rows` rows (co-linear batching, Algorithm 5; W and H
+ * stay resident on the device).  Each sweep uploads A once: a batch first gets
+ * its W rows updated with the current H, then contributes W_b^T A_b and
+ * W_b^T W_b of the updated rows to the next H update.  iters iterations take
+ * iters + 1 sweeps and give the same sequence H1, W1, H2, W2, ... as
+ * nmf_mu_dense.
+ *   A_host               host, m x n; pinned memory is needed for copies to
+ *                        overlap with compute (pageable memory works, slowly)
+ *   batch_rows           >= 1, need not divide m
+ *   device_budget_bytes  upper bound on device memory used to stage A; the
+ *                        library uses min(3, what fits) staging slots of
+ *                        batch_rows x n floats and fails with NMF_ENOMEM if not
+ *                        even one fits
+ */
+int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k,
+               float *W, float *H, int32_t iters, float eps,
+               int64_t batch_rows, int64_t device_budget_bytes, void *stream);
+
+/*
+ * Ensemble of independent resident dense runs of one shape (the perturbed
+ * copies times rank sweep that model selection needs, sections 1 and 4.5).
+ * Run r factorises A[r] (m x n) with rank k[r] into W[r] (m x k[r]) and H[r]
+ * (k[r] x n).  A[r] may be the same pointer for several runs; W[r], H[r] must
+ * not overlap.  The pointer arrays and k live in HOST memory and are read
+ * before the call returns; what they point to is device memory.
+ */
+int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64_t n,
+                         const int32_t *k, float *const *W, float *const *H,
+                         int32_t iters, float eps, void *stream);
+
+/*
+ * Workspace the given problem needs, in bytes (kind: 0 dense, 1 csr, 2 ooc
+ * [excluding the staging slots], 3 batched with k = largest rank).  0 on
+ * invalid arguments.
+ */
+size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz,
+                              int32_t k, int64_t batch_rows);
+
+/*
+ * Hand the library a device block to use as its workspace instead of its own
+ * allocation (dev_ptr == NULL or bytes == 0 returns to library-owned memory).
+ * The block must stay valid until replaced; 256-byte alignment required.
+ */
+int nmf_mu_set_workspace(void *dev_ptr, size_t bytes);
+
+/* Free library-owned workspace and staging memory (synchronises the device). */
+int nmf_mu_release(void);
+
+/* ---- single steps, exposed for testing and profiling (same conventions) ---- */
+
+/* G (k x k, ld k) = W^T W.  Algorithm 3, formation of WTW. */
+int nmf_gram_w(const float *W, int64_t m, int32_t k, float *G, void *stream);
+
+/* P (k x n, ld n) = W^T A for dense A.  Algorithm 3, formation of WTA. */
+int nmf_wta_dense(const float *A, int64_t m, int64_t n, int32_t k,
+                  const float *W, float *P, void *stream);
+
+/* H <- H * P / (G H + eps) in place and GH (k x k) = H H^T of the new H.
+ * Algorithm 3, the H-update line and the formation of HHT.  GH may be NULL. */
+int nmf_h_update(float *H, const float *P, const float *G, int32_t k, int64_t n,
+                 float eps, float *GH, void *stream);
+
+/* W <- W * (A H^T) / (W GH + eps) in place, A dense.  Algorithm 3, formation
+ * of AHT and WHHT and the W-update line, fused. */
+int nmf_aht_w_update_dense(const float *A, int64_t m, int64_t n, int32_t k,
+                           const float *H, const float *GH, float *W,
+                           float eps, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NMFMU_H */

@@ -1,0 +1,425 @@
+// C ABI of libnmfmu: argument checking, workspace management and the host-side
+// schedules (resident loop, out-of-memory batch pipeline, CSR loop, ensemble).
+// Public contract: include/nmfmu.h.
+#include "nmfmu.h"
+#include "nmfmu_internal.h"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <mutex>
+
+using namespace nmfmu;
+
+namespace {
+
+thread_local char t_err[256] = "";
+
+int fail(int status, const char *fmt, const char *detail = "")
+{
+    snprintf(t_err, sizeof(t_err), fmt, detail);
+    return status;
+}
+
+#define NMF_HIP(call)                                                         \
+    do {                                                                      \
+        hipError_t e_ = (call);                                               \
+        if (e_ != hipSuccess) return fail(NMF_EHIP, #call ": %s", hipGetErrorString(e_)); \
+    } while (0)
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// ---- process-wide device memory owned by the library ----------------------
+
+struct State {
+    std::mutex mu;
+    void *ws = nullptr;         // workspace in use (owned or caller's)
+    size_t ws_bytes = 0;
+    bool ws_owned = true;
+    void *stage = nullptr;      // staging slots of the out-of-memory path
+    size_t stage_bytes = 0;
+    hipStream_t copy_stream = nullptr;
+    hipEvent_t ev_copied[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t ev_freed[3] = {nullptr, nullptr, nullptr};
+    hipEvent_t ev_entry = nullptr;
+};
+State g;
+
+// Workspace carving.  Slot 0 holds the arrival counters of the Gram kernels and
+// must be zero whenever no kernel is running; the kernels restore that.
+struct Carve {
+    char *base;
+    size_t off = 0;
+    explicit Carve(void *b) : base(static_cast<char *>(b)) {}
+    template <class T> T *take(size_t count)
+    {
+        T *p = reinterpret_cast<T *>(base + off);
+        off = align_up(off + count * sizeof(T));
+        return p;
+    }
+};
+
+struct Common {
+    unsigned *counters;
+    float *gw, *gh, *gpart;
+};
+
+Common carve_common(Carve &c, int k)
+{
+    Common r;
+    r.counters = c.take<unsigned>(64);
+    r.gw = c.take<float>((size_t)k * k);
+    r.gh = c.take<float>((size_t)k * k);
+    const int kt = k_tiles(k);
+    r.gpart = c.take<float>((size_t)kGramMaxBlocks * kt * kt * 1024);
+    return r;
+}
+
+size_t common_bytes(int k)
+{
+    Carve c(nullptr);
+    carve_common(c, k);
+    return c.off;
+}
+
+int ensure_workspace(size_t need, void **out)
+{
+    if (g.ws && g.ws_bytes >= need) {
+        *out = g.ws;
+        return NMF_OK;
+    }
+    if (!g.ws_owned) return fail(NMF_ENOMEM, "caller-provided workspace is too small%s");
+    if (g.ws) {
+        NMF_HIP(hipDeviceSynchronize());
+        NMF_HIP(hipFree(g.ws));
+        g.ws = nullptr;
+        g.ws_bytes = 0;
+    }
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, need);
+    if (e != hipSuccess) return fail(NMF_ENOMEM, "hipMalloc(workspace): %s", hipGetErrorString(e));
+    NMF_HIP(hipMemset(p, 0, kAlign));
+    g.ws = p;
+    g.ws_bytes = need;
+    *out = p;
+    return NMF_OK;
+}
+
+int check_common(const void *a, const void *w, const void *h, int64_t m, int64_t n, int32_t k,
+                 int32_t iters, float eps)
+{
+    if (!a || !w || !h) return fail(NMF_EINVAL, "null pointer%s");
+    if (m < 1 || n < 1 || k < 1) return fail(NMF_EINVAL, "m, n, k must be >= 1%s");
+    if (k > NMF_MU_MAX_K) return fail(NMF_EUNSUPPORTED, "k exceeds NMF_MU_MAX_K%s");
+    if (iters < 0) return fail(NMF_EINVAL, "iters must be >= 0%s");
+    if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(NMF_EINVAL, "eps must be finite and >= 0%s");
+    if (m > (int64_t)1 << 40 || n > (int64_t)1 << 31) return fail(NMF_EINVAL, "matrix too large%s");
+    return NMF_OK;
+}
+
+// One resident dense run on `st` with a workspace already carved.
+int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, int iters,
+               float eps, const Common &c, float *ppart, hipStream_t st)
+{
+    const int splits = wta_splits(m, n);
+    const int64_t rps = wta_rows_per_split(m, splits);
+    for (int it = 0; it < iters; ++it) {
+        NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+        NMF_HIP(launch_wta_pass(A, m, n, k, W, ppart, splits, rps, false, st));
+        NMF_HIP(launch_h_update(H, ppart, splits, c.gw, k, n, eps, st));
+        NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
+        NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
+    }
+    return NMF_OK;
+}
+
+size_t dense_bytes(int64_t m, int64_t n, int k)
+{
+    return common_bytes(k) + align_up((size_t)wta_splits(m, n) * k * n * sizeof(float));
+}
+
+size_t csr_bytes(int64_t n, int k) { return common_bytes(k) + 2 * align_up((size_t)n * k * sizeof(float)); }
+
+}  // namespace
+
+extern "C" {
+
+const char *nmf_status_string(int status)
+{
+    switch (status) {
+    case NMF_OK: return "NMF_OK";
+    case NMF_EINVAL: return "NMF_EINVAL";
+    case NMF_ENOMEM: return "NMF_ENOMEM";
+    case NMF_EHIP: return "NMF_EHIP";
+    case NMF_EUNSUPPORTED: return "NMF_EUNSUPPORTED";
+    default: return "NMF_UNKNOWN";
+    }
+}
+
+const char *nmf_last_error(void) { return t_err; }
+
+size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz, int32_t k,
+                              int64_t batch_rows)
+{
+    (void)nnz;
+    if (m < 1 || n < 1 || k < 1 || k > NMF_MU_MAX_K) return 0;
+    switch (kind) {
+    case 0:
+    case 3: return dense_bytes(m, n, k);
+    case 1: return csr_bytes(n, k);
+    case 2:
+        if (batch_rows < 1) return 0;
+        return dense_bytes(batch_rows < m ? batch_rows : m, n, k);
+    default: return 0;
+    }
+}
+
+int nmf_mu_set_workspace(void *dev_ptr, size_t bytes)
+{
+    std::lock_guard<std::mutex> lock(g.mu);
+    if (dev_ptr && bytes) {
+        if (reinterpret_cast<uintptr_t>(dev_ptr) % kAlign) return fail(NMF_EINVAL, "workspace must be 256-byte aligned%s");
+        if (bytes < kAlign) return fail(NMF_EINVAL, "workspace too small%s");
+        if (g.ws && g.ws_owned) {
+            NMF_HIP(hipDeviceSynchronize());
+            NMF_HIP(hipFree(g.ws));
+        }
+        NMF_HIP(hipMemset(dev_ptr, 0, kAlign));
+        g.ws = dev_ptr;
+        g.ws_bytes = bytes;
+        g.ws_owned = false;
+    } else {
+        if (!g.ws_owned) {
+            g.ws = nullptr;
+            g.ws_bytes = 0;
+        }
+        g.ws_owned = true;
+    }
+    return NMF_OK;
+}
+
+int nmf_mu_release(void)
+{
+    std::lock_guard<std::mutex> lock(g.mu);
+    NMF_HIP(hipDeviceSynchronize());
+    if (g.ws && g.ws_owned) NMF_HIP(hipFree(g.ws));
+    if (g.ws_owned) {
+        g.ws = nullptr;
+        g.ws_bytes = 0;
+    }
+    if (g.stage) NMF_HIP(hipFree(g.stage));
+    g.stage = nullptr;
+    g.stage_bytes = 0;
+    for (int i = 0; i < 3; ++i) {
+        if (g.ev_copied[i]) NMF_HIP(hipEventDestroy(g.ev_copied[i]));
+        if (g.ev_freed[i]) NMF_HIP(hipEventDestroy(g.ev_freed[i]));
+        g.ev_copied[i] = g.ev_freed[i] = nullptr;
+    }
+    if (g.ev_entry) NMF_HIP(hipEventDestroy(g.ev_entry));
+    g.ev_entry = nullptr;
+    if (g.copy_stream) NMF_HIP(hipStreamDestroy(g.copy_stream));
+    g.copy_stream = nullptr;
+    return NMF_OK;
+}
+
+int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                 int32_t iters, float eps, void *stream)
+{
+    if (int rc = check_common(A, W, H, m, n, k, iters, eps)) return rc;
+    if (iters == 0) return NMF_OK;
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(dense_bytes(m, n, k), &ws)) return rc;
+    Carve cv(ws);
+    const Common c = carve_common(cv, k);
+    float *ppart = cv.take<float>((size_t)wta_splits(m, n) * k * n);
+    return dense_body(A, m, n, k, W, H, iters, eps, c, ppart, static_cast<hipStream_t>(stream));
+}
+
+int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64_t n,
+                         const int32_t *k, float *const *W, float *const *H, int32_t iters,
+                         float eps, void *stream)
+{
+    if (n_runs < 0 || !A || !k || !W || !H) return fail(NMF_EINVAL, "null pointer or negative run count%s");
+    int kmax = 1;
+    for (int r = 0; r < n_runs; ++r) {
+        if (int rc = check_common(A[r], W[r], H[r], m, n, k[r], iters, eps)) return rc;
+        if (k[r] > kmax) kmax = k[r];
+    }
+    if (iters == 0 || n_runs == 0) return NMF_OK;
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(dense_bytes(m, n, kmax), &ws)) return rc;
+    for (int r = 0; r < n_runs; ++r) {
+        Carve cv(ws);
+        const Common c = carve_common(cv, k[r]);
+        float *ppart = cv.take<float>((size_t)wta_splits(m, n) * k[r] * n);
+        if (int rc = dense_body(A[r], m, n, k[r], W[r], H[r], iters, eps, c, ppart,
+                                static_cast<hipStream_t>(stream)))
+            return rc;
+    }
+    return NMF_OK;
+}
+
+int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, float *H,
+               int32_t iters, float eps, int64_t batch_rows, int64_t device_budget_bytes,
+               void *stream)
+{
+    if (int rc = check_common(A_host, W, H, m, n, k, iters, eps)) return rc;
+    if (batch_rows < 1) return fail(NMF_EINVAL, "batch_rows must be >= 1%s");
+    if (device_budget_bytes < 1) return fail(NMF_EINVAL, "device_budget_bytes must be >= 1%s");
+    if (iters == 0) return NMF_OK;
+    if (batch_rows > m) batch_rows = m;
+    const size_t slot_bytes = align_up((size_t)batch_rows * n * sizeof(float));
+    int slots = (int)((size_t)device_budget_bytes / slot_bytes);
+    if (slots < 1) return fail(NMF_ENOMEM, "device budget does not hold one batch%s");
+    if (slots > 3) slots = 3;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(dense_bytes(batch_rows, n, k), &ws)) return rc;
+    Carve cv(ws);
+    const Common c = carve_common(cv, k);
+    const int splits = wta_splits(batch_rows, n);
+    const int64_t rps = wta_rows_per_split(batch_rows, splits);
+    float *ppart = cv.take<float>((size_t)splits * k * n);
+
+    if (g.stage_bytes < slots * slot_bytes) {
+        if (g.stage) {
+            NMF_HIP(hipDeviceSynchronize());
+            NMF_HIP(hipFree(g.stage));
+            g.stage = nullptr;
+            g.stage_bytes = 0;
+        }
+        hipError_t e = hipMalloc(&g.stage, slots * slot_bytes);
+        if (e != hipSuccess) return fail(NMF_ENOMEM, "hipMalloc(staging): %s", hipGetErrorString(e));
+        g.stage_bytes = slots * slot_bytes;
+    }
+    if (!g.copy_stream) {
+        NMF_HIP(hipStreamCreateWithFlags(&g.copy_stream, hipStreamNonBlocking));
+        for (int i = 0; i < 3; ++i) {
+            NMF_HIP(hipEventCreateWithFlags(&g.ev_copied[i], hipEventDisableTiming));
+            NMF_HIP(hipEventCreateWithFlags(&g.ev_freed[i], hipEventDisableTiming));
+        }
+        NMF_HIP(hipEventCreateWithFlags(&g.ev_entry, hipEventDisableTiming));
+    }
+    // Staging slots may still be read by work enqueued earlier on `st`.
+    NMF_HIP(hipEventRecord(g.ev_entry, st));
+    NMF_HIP(hipStreamWaitEvent(g.copy_stream, g.ev_entry, 0));
+
+    const int64_t nb = (m + batch_rows - 1) / batch_rows;
+    int64_t issued = 0;   // batches handed to the copy stream so far, over all sweeps
+    for (int s = 0; s <= iters; ++s) {
+        for (int64_t b = 0; b < nb; ++b, ++issued) {
+            const int slot = (int)(issued % slots);
+            const int64_t i0 = b * batch_rows;
+            const int64_t rb = (i0 + batch_rows <= m) ? batch_rows : m - i0;
+            float *Ab = reinterpret_cast<float *>(static_cast<char *>(g.stage) + slot * slot_bytes);
+            if (issued >= slots) NMF_HIP(hipStreamWaitEvent(g.copy_stream, g.ev_freed[slot], 0));
+            NMF_HIP(hipMemcpyAsync(Ab, A_host + i0 * n, (size_t)rb * n * sizeof(float),
+                                   hipMemcpyHostToDevice, g.copy_stream));
+            NMF_HIP(hipEventRecord(g.ev_copied[slot], g.copy_stream));
+            NMF_HIP(hipStreamWaitEvent(st, g.ev_copied[slot], 0));
+            if (s > 0) NMF_HIP(launch_aht_pass(Ab, rb, n, k, H, c.gh, W + i0 * k, eps, st));
+            if (s < iters)
+                NMF_HIP(launch_wta_pass(Ab, rb, n, k, W + i0 * k, ppart, splits, rps, b > 0, st));
+            NMF_HIP(hipEventRecord(g.ev_freed[slot], st));
+        }
+        if (s < iters) {
+            NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+            NMF_HIP(launch_h_update(H, ppart, splits, c.gw, k, n, eps, st));
+            NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
+        }
+    }
+    return NMF_OK;
+}
+
+int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
+               int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t iters, float eps,
+               void *stream)
+{
+    if (!rowptr) return fail(NMF_EINVAL, "null pointer%s");
+    if (nnz < 0) return fail(NMF_EINVAL, "nnz must be >= 0%s");
+    if (nnz > 0 && (!colidx || !vals)) return fail(NMF_EINVAL, "null pointer%s");
+    if (int rc = check_common(rowptr, W, H, m, n, k, iters, eps)) return rc;
+    if (iters == 0) return NMF_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(csr_bytes(n, k), &ws)) return rc;
+    Carve cv(ws);
+    const Common c = carve_common(cv, k);
+    float *Ht = cv.take<float>((size_t)n * k);
+    float *Pt = cv.take<float>((size_t)n * k);
+
+    NMF_HIP(launch_transpose(H, k, n, Ht, st));
+    for (int it = 0; it < iters; ++it) {
+        NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+        NMF_HIP(launch_fill_zero(Pt, n * k, st));
+        NMF_HIP(launch_wta_csr(rowptr, colidx, vals, m, k, W, Pt, st));
+        NMF_HIP(launch_row_update(Ht, Pt, c.gw, n, k, eps, st));
+        NMF_HIP(launch_gram_w(Ht, n, k, c.gh, c.gpart, c.counters, st));
+        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, m, k, Ht, c.gh, W, eps, st));
+    }
+    NMF_HIP(launch_transpose(Ht, n, k, H, st));
+    return NMF_OK;
+}
+
+// ---- single steps ----------------------------------------------------------
+
+int nmf_gram_w(const float *W, int64_t m, int32_t k, float *G, void *stream)
+{
+    if (int rc = check_common(W, W, G, m, 1, k, 0, 0.f)) return rc;
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(common_bytes(k), &ws)) return rc;
+    Carve cv(ws);
+    const Common c = carve_common(cv, k);
+    NMF_HIP(launch_gram_w(W, m, k, G, c.gpart, c.counters, static_cast<hipStream_t>(stream)));
+    return NMF_OK;
+}
+
+int nmf_wta_dense(const float *A, int64_t m, int64_t n, int32_t k, const float *W, float *P,
+                  void *stream)
+{
+    if (int rc = check_common(A, W, P, m, n, k, 0, 0.f)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(dense_bytes(m, n, k), &ws)) return rc;
+    Carve cv(ws);
+    carve_common(cv, k);
+    const int splits = wta_splits(m, n);
+    float *ppart = cv.take<float>((size_t)splits * k * n);
+    NMF_HIP(launch_wta_pass(A, m, n, k, W, ppart, splits, wta_rows_per_split(m, splits), false, st));
+    NMF_HIP(launch_sum_partials(ppart, splits, (int64_t)k * n, P, st));
+    return NMF_OK;
+}
+
+int nmf_h_update(float *H, const float *P, const float *G, int32_t k, int64_t n, float eps,
+                 float *GH, void *stream)
+{
+    if (int rc = check_common(H, P, G, 1, n, k, 0, eps)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(common_bytes(k), &ws)) return rc;
+    Carve cv(ws);
+    const Common c = carve_common(cv, k);
+    NMF_HIP(launch_h_update(H, P, 1, G, k, n, eps, st));
+    if (GH) NMF_HIP(launch_gram_h(H, k, n, GH, c.gpart, c.counters, st));
+    return NMF_OK;
+}
+
+int nmf_aht_w_update_dense(const float *A, int64_t m, int64_t n, int32_t k, const float *H,
+                           const float *GH, float *W, float eps, void *stream)
+{
+    if (int rc = check_common(A, W, H, m, n, k, 0, eps)) return rc;
+    if (!GH) return fail(NMF_EINVAL, "null pointer%s");
+    NMF_HIP(launch_aht_pass(A, m, n, k, H, GH, W, eps, static_cast<hipStream_t>(stream)));
+    return NMF_OK;
+}
+
+}  // extern "C"

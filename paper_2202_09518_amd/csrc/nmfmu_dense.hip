@@ -1,0 +1,516 @@
+// Dense kernels of the multiplicative-update iteration for gfx950 (MI355X).
+//
+// One iteration (paper, Algorithm 3 on a single unit) is five launches:
+//   gram_w   : WTW  = W^T W                       (k x k)
+//   wta_pass : WTA  = W^T A, as row-split partials (reads all of A)
+//   h_update : H   <- H * WTA / (WTW H + eps)
+//   gram_h   : HHT  = H H^T of the new H          (k x k)
+//   aht_pass : W   <- W * (A H^T) / (W HHT + eps) (reads all of A; A H^T and
+//              W HHT are never stored)
+//
+// Both passes over A are fp32 contractions with a small rank k, done on the
+// matrix cores with v_mfma_f32_32x32x2_f32: one instruction multiplies a
+// 32 x 2 by a 2 x 32 fp32 tile into a 32 x 32 fp32 accumulator and consumes
+// 64 elements of A, which at full issue rate is about what HBM delivers, so
+// the passes stay bandwidth bound.  A is read straight from global memory
+// into the operand registers (every element of A feeds exactly one
+// instruction, so staging it in LDS would buy nothing); LDS is used for the
+// cross-wave reductions and the fused update epilogue.
+//
+// Lane layout of v_mfma_f32_32x32x2_f32 (64 lanes, D = A_op B_op + C):
+//   A_op (32 x 2):  lane l holds A_op[l % 32][l / 32]
+//   B_op (2 x 32):  lane l holds B_op[l / 32][l % 32]
+//   D    (32 x 32): lane l, register v holds D[(v % 4) + 4 (l / 32) + 8 (v / 4)][l % 32]
+#include "nmfmu_internal.h"
+
+namespace nmfmu {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+// Row of the 32 x 32 accumulator held in register v of a lane in half `half`.
+__device__ __forceinline__ int acc_row(int v, int half) { return (v & 3) + 4 * half + 8 * (v >> 2); }
+
+// Four consecutive elements X[row][col .. col+3] of a row-major matrix with
+// `ncols` columns; elements outside the matrix (or the whole group, if !ok)
+// read as zero.  VEC needs a 16-byte aligned base and ncols % 4 == 0, col % 4 == 0.
+template <bool VEC>
+__device__ __forceinline__ f32x4 load4(const float *__restrict__ X, int64_t ncols, int64_t row,
+                                       int64_t col, bool ok)
+{
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (VEC) {
+        if (ok && col < ncols) v = *reinterpret_cast<const f32x4 *>(X + row * ncols + col);
+    } else {
+        if (ok) {
+            const float *p = X + row * ncols + col;
+            if (col + 0 < ncols) v.x = p[0];
+            if (col + 1 < ncols) v.y = p[1];
+            if (col + 2 < ncols) v.z = p[2];
+            if (col + 3 < ncols) v.w = p[3];
+        }
+    }
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// Gram matrices.  MODE 0: G = X^T X, X is rows x k (the factor W).
+//                 MODE 1: G = X X^T, X is k x cols (the factor H).
+// blockIdx.y selects one 32 x 32 tile (t1, t2) of G; every block sums a slice
+// of the long dimension, writes its partial tile, and the block that arrives
+// last adds the partials in block order (deterministic) and stores G.
+// ---------------------------------------------------------------------------
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ X, int64_t len, int k,
+                                                   float *__restrict__ G, float *gpart,
+                                                   unsigned *counters)
+{
+    constexpr int NW = 4;
+    __shared__ float red[1024];
+    __shared__ unsigned ticket_s;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int jj = lane & 31, half = lane >> 5;
+    const int kt = (k + 31) >> 5;
+    const int t1 = blockIdx.y / kt, t2 = blockIdx.y % kt;
+    const int c1 = 32 * t1 + jj, c2 = 32 * t2 + jj;
+    const int64_t gw = (int64_t)blockIdx.x * NW + w, tw = (int64_t)gridDim.x * NW;
+
+    f32x16 acc = {0};
+    if (MODE == 0) {
+        const int64_t npairs = (len + 1) >> 1;
+        for (int64_t p = gw; p < npairs; p += tw) {
+            const int64_t row = 2 * p + half;
+            const bool ok = row < len;
+            const float a = (ok && c1 < k) ? X[row * k + c1] : 0.f;
+            const float b = (ok && c2 < k) ? X[row * k + c2] : 0.f;
+            acc = mfma32(a, b, acc);
+        }
+    } else {
+        const int64_t ngroups = (len + 7) >> 3;
+        for (int64_t g = gw; g < ngroups; g += tw) {
+            const int64_t col = 8 * g + 4 * half;
+            const f32x4 a = load4<VEC>(X, len, c1, col, c1 < k);
+            const f32x4 b = load4<VEC>(X, len, c2, col, c2 < k);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc = mfma32(a[q], b[q], acc);
+        }
+    }
+
+    // Sum the four waves in wave order.
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                if (ww == 0) red[v * 64 + lane] = acc[v];
+                else red[v * 64 + lane] += acc[v];
+            }
+        }
+        __syncthreads();
+    }
+    const int ntiles = gridDim.y;
+    float *mine = gpart + ((int64_t)blockIdx.x * ntiles + blockIdx.y) * 1024;
+    for (int e = tid; e < 1024; e += 256) mine[e] = red[e];
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) ticket_s = atomicAdd(&counters[blockIdx.y], 1u);
+    __syncthreads();
+    if (ticket_s != gridDim.x - 1) return;
+    __threadfence();
+    for (int e = tid; e < 1024; e += 256) {
+        float s = 0.f;
+        for (unsigned b = 0; b < gridDim.x; ++b) {
+            const float *src = gpart + ((int64_t)b * ntiles + blockIdx.y) * 1024 + e;
+            s += __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        const int v = e >> 6, l = e & 63;
+        const int r1 = 32 * t1 + acc_row(v, l >> 5), r2 = 32 * t2 + (l & 31);
+        if (r1 < k && r2 < k) G[r1 * k + r2] = s;
+    }
+    if (tid == 0) counters[blockIdx.y] = 0u;
+}
+
+// ---------------------------------------------------------------------------
+// W^T A pass.  Workgroup = 8 waves on one 128-column slab of A and one row
+// split; wave w takes row pairs w, w+8, ... of the split.  Per row pair a lane
+// loads four consecutive columns (one 16-byte load, 512 contiguous bytes per
+// row and wave) and one element of each W row; column tile q of the wave
+// therefore holds columns j0 + 4 jj + q.  MFMA roles: A_op = W rows (factor
+// index across lanes), B_op = A elements (column across lanes), reduction
+// over the two rows.  The eight waves are summed through LDS in wave order and
+// the slab is written (or added) to the split's partial result.
+// ---------------------------------------------------------------------------
+template <int KT, int U, bool VEC>
+__global__ __launch_bounds__(512) void wta_pass_kernel(const float *__restrict__ A,
+                                                       const float *__restrict__ W,
+                                                       float *__restrict__ ppart, int64_t rows,
+                                                       int64_t n, int k, int64_t rps,
+                                                       int accumulate)
+{
+    constexpr int NW = kWtaWaves;
+    constexpr int LD = 132;
+    __shared__ float red[KT * 32 * LD];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int jj = lane & 31, half = lane >> 5;
+    const int64_t j0 = (int64_t)blockIdx.x * kWtaCols;
+    const int64_t col = j0 + 4 * jj;
+    const int64_t r0 = (int64_t)blockIdx.y * rps;
+    const int64_t r1 = (r0 + rps < rows) ? r0 + rps : rows;
+
+    f32x16 acc[KT][4];
+#pragma unroll
+    for (int t = 0; t < KT; ++t)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[t][q] = f32x16{0};
+
+    struct Stage {
+        f32x4 a[U];
+        float wv[U][KT];
+    };
+    auto load_stage = [&](Stage &s, int64_t ibase) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int64_t row = ibase + 2 * NW * u + half;
+            const bool ok = row < r1;
+            s.a[u] = load4<VEC>(A, n, row, col, ok);
+#pragma unroll
+            for (int t = 0; t < KT; ++t) {
+                const int c = 32 * t + jj;
+                s.wv[u][t] = (ok && c < k) ? W[row * k + c] : 0.f;
+            }
+        }
+    };
+    const int64_t step = 2 * NW * U;
+    Stage cur, nxt;
+    int64_t i = r0 + 2 * w;
+    load_stage(cur, i);
+    for (; i < r1; i += step) {
+        load_stage(nxt, i + step);
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    acc[t][q] = mfma32(cur.wv[u][t], cur.a[u][q], acc[t][q]);
+        cur = nxt;
+    }
+
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int t = 0; t < KT; ++t)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int idx = (32 * t + acc_row(v, half)) * LD + q * 32 + jj;
+                        if (ww == 0) red[idx] = acc[t][q][v];
+                        else red[idx] += acc[t][q][v];
+                    }
+        }
+        __syncthreads();
+    }
+    float *dst = ppart + (int64_t)blockIdx.y * k * n;
+    for (int e = tid; e < k * kWtaCols; e += 512) {
+        const int c = e >> 7, x = e & 127;
+        const int64_t cj = j0 + x;
+        if (cj < n) {
+            float val = red[c * LD + (x & 3) * 32 + (x >> 2)];
+            float *p = dst + (int64_t)c * n + cj;
+            if (accumulate) val += *p;
+            *p = val;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// H update: one thread per column j.  The old column is held in registers, so
+// the column can be overwritten factor by factor.
+// ---------------------------------------------------------------------------
+template <int KP>
+__global__ __launch_bounds__(256) void h_update_kernel(float *H, const float *__restrict__ ppart,
+                                                       int splits, const float *__restrict__ G,
+                                                       int k, int64_t n, float eps)
+{
+    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < n; j += (int64_t)gridDim.x * 256) {
+        float h[KP];
+#pragma unroll
+        for (int d = 0; d < KP; ++d) h[d] = (d < k) ? H[(int64_t)d * n + j] : 0.f;
+        for (int c = 0; c < k; ++c) {
+            float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+#pragma unroll
+            for (int d = 0; d < KP; d += 4) {
+                d0 += ((d + 0 < k) ? G[c * k + d + 0] : 0.f) * h[d + 0];
+                d1 += ((d + 1 < k) ? G[c * k + d + 1] : 0.f) * h[d + 1];
+                d2 += ((d + 2 < k) ? G[c * k + d + 2] : 0.f) * h[d + 2];
+                d3 += ((d + 3 < k) ? G[c * k + d + 3] : 0.f) * h[d + 3];
+            }
+            const float den = ((d0 + d1) + (d2 + d3)) + eps;
+            float p = 0.f;
+            for (int s = 0; s < splits; ++s) p += ppart[((int64_t)s * k + c) * n + j];
+            const int64_t at = (int64_t)c * n + j;
+            H[at] = H[at] * p / den;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// A H^T pass with the W update fused.  Workgroup = 8 waves on RT*32 rows of A;
+// the waves split the columns in groups of 32 (one 128-byte line per row).
+// MFMA roles: A_op = A elements (row across lanes), B_op = H elements (factor
+// index across lanes), reduction over two columns; a lane's 16-byte load gives
+// four instructions their operands, so both A and H are read with the same
+// pattern: lane l, load u -> row l % 32, columns jb + 8u + 4 (l / 32) .. +3.
+// Epilogue: waves summed through LDS in wave order, then
+//   W[i][c] <- W[i][c] * Q[i][c] / (sum_d W[i][d] GH[d][c] + eps).
+// ---------------------------------------------------------------------------
+template <int KT, int RT, bool VEC>
+__global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__ A,
+                                                       const float *__restrict__ H,
+                                                       const float *__restrict__ GH, float *W,
+                                                       int64_t rows, int64_t n, int k, float eps)
+{
+    constexpr int NW = kAhtWaves;
+    constexpr int RB = 32 * RT;
+    constexpr int KP = 32 * KT;
+    constexpr int LDQ = KP + 1;
+    __shared__ float Qs[RB * LDQ];
+    __shared__ float Ws[RB * LDQ];
+    __shared__ float Gs[KP * LDQ];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int r = lane & 31, half = lane >> 5;
+    const int64_t i0 = (int64_t)blockIdx.x * RB;
+
+    // Stage GH (zero padded) and the old W rows of this block.
+    for (int e = tid; e < KP * KP; e += 512) {
+        const int d = e / KP, c = e % KP;
+        Gs[d * LDQ + c] = (d < k && c < k) ? GH[d * k + c] : 0.f;
+    }
+    for (int e = tid; e < RB * KP; e += 512) {
+        const int i = e / KP, c = e % KP;
+        Ws[i * LDQ + c] = (i0 + i < rows && c < k) ? W[(i0 + i) * k + c] : 0.f;
+    }
+
+    int64_t arow[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int64_t row = i0 + 32 * rt + r;
+        arow[rt] = (row < rows) ? row : rows - 1;   // clamped rows are discarded below
+    }
+
+    f32x16 acc[RT][KT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int t = 0; t < KT; ++t) acc[rt][t] = f32x16{0};
+
+    struct Stage {
+        f32x4 a[RT][4];
+        f32x4 h[KT][4];
+    };
+    auto load_stage = [&](Stage &s, int64_t g) {
+        const int64_t jb = 32 * g + 4 * half;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) s.a[rt][u] = load4<VEC>(A, n, arow[rt], jb + 8 * u, true);
+#pragma unroll
+            for (int t = 0; t < KT; ++t) s.h[t][u] = load4<VEC>(H, n, 32 * t + r, jb + 8 * u, 32 * t + r < k);
+        }
+    };
+    const int64_t ngroups = (n + 31) >> 5;
+    Stage cur, nxt;
+    int64_t g = w;
+    load_stage(cur, g);
+    for (; g < ngroups; g += NW) {
+        load_stage(nxt, g + NW);   // columns >= n read as zero, no memory access
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                    for (int t = 0; t < KT; ++t)
+                        acc[rt][t] = mfma32(cur.a[rt][u][q], cur.h[t][u][q], acc[rt][t]);
+        cur = nxt;
+    }
+
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+                for (int t = 0; t < KT; ++t)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int idx = (32 * rt + acc_row(v, half)) * LDQ + 32 * t + r;
+                        if (ww == 0) Qs[idx] = acc[rt][t][v];
+                        else Qs[idx] += acc[rt][t][v];
+                    }
+        }
+        __syncthreads();
+    }
+
+    for (int e = tid; e < RB * k; e += 512) {
+        const int i = e / k, c = e % k;
+        if (i0 + i < rows) {
+            float d0 = 0.f, d1 = 0.f;
+            for (int d = 0; d + 1 < k; d += 2) {
+                d0 += Ws[i * LDQ + d] * Gs[d * LDQ + c];
+                d1 += Ws[i * LDQ + d + 1] * Gs[(d + 1) * LDQ + c];
+            }
+            if (k & 1) d0 += Ws[i * LDQ + k - 1] * Gs[(k - 1) * LDQ + c];
+            const float den = (d0 + d1) + eps;
+            W[(i0 + i) * k + c] = Ws[i * LDQ + c] * Qs[i * LDQ + c] / den;
+        }
+    }
+}
+
+// P = sum over the row splits of the partial W^T A results (test entry point only).
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float *__restrict__ ppart,
+                                                           int splits, int64_t count,
+                                                           float *__restrict__ P)
+{
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256) {
+        float s = 0.f;
+        for (int t = 0; t < splits; ++t) s += ppart[(int64_t)t * count + e];
+        P[e] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Host side launchers
+// ---------------------------------------------------------------------------
+
+static inline bool vec_ok(const void *p, int64_t ld)
+{
+    return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld & 3) == 0;
+}
+
+int wta_splits(int64_t rows, int64_t n)
+{
+    const int64_t slabs = (n + kWtaCols - 1) / kWtaCols;
+    int64_t s = (2048 + slabs - 1) / slabs;          // aim at >= 2048 workgroups
+    const int64_t max_by_rows = (rows + 127) / 128;  // at least 128 rows per split
+    if (s > max_by_rows) s = max_by_rows;
+    if (s > 32) s = 32;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+int64_t wta_rows_per_split(int64_t rows, int splits)
+{
+    int64_t rps = (rows + splits - 1) / splits;
+    return (rps + 1) & ~(int64_t)1;   // even, so that a row pair never straddles a split
+}
+
+static int gram_blocks(int64_t len, int per_block)
+{
+    int64_t b = (len + per_block - 1) / per_block;
+    if (b > kGramMaxBlocks) b = kGramMaxBlocks;
+    if (b < 1) b = 1;
+    return (int)b;
+}
+
+hipError_t launch_gram_w(const float *X, int64_t rows, int k, float *G, float *gpart,
+                         unsigned *counters, hipStream_t st)
+{
+    const int kt = k_tiles(k);
+    dim3 grid(gram_blocks(rows, 512), kt * kt);
+    hipLaunchKernelGGL((gram_kernel<0, false>), grid, dim3(256), 0, st, X, rows, k, G, gpart, counters);
+    return hipGetLastError();
+}
+
+hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *gpart,
+                         unsigned *counters, hipStream_t st)
+{
+    const int kt = k_tiles(k);
+    dim3 grid(gram_blocks(cols, 1024), kt * kt);
+    if (vec_ok(X, cols))
+        hipLaunchKernelGGL((gram_kernel<1, true>), grid, dim3(256), 0, st, X, cols, k, G, gpart, counters);
+    else
+        hipLaunchKernelGGL((gram_kernel<1, false>), grid, dim3(256), 0, st, X, cols, k, G, gpart, counters);
+    return hipGetLastError();
+}
+
+template <int KT>
+static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *W,
+                         float *ppart, int64_t rows, int64_t n, int k, int64_t rps, int acc)
+{
+    constexpr int U = 4;
+    if (vec)
+        hipLaunchKernelGGL((wta_pass_kernel<KT, U, true>), grid, dim3(512), 0, st, A, W, ppart, rows, n, k, rps, acc);
+    else
+        hipLaunchKernelGGL((wta_pass_kernel<KT, U, false>), grid, dim3(512), 0, st, A, W, ppart, rows, n, k, rps, acc);
+}
+
+hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
+                           float *ppart, int splits, int64_t rps, bool accumulate, hipStream_t st)
+{
+    dim3 grid((unsigned)((n + kWtaCols - 1) / kWtaCols), (unsigned)splits);
+    const bool vec = vec_ok(A, n);
+    const int acc = accumulate ? 1 : 0;
+    switch (k_tiles(k)) {
+    case 1: wta_dispatch<1>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc); break;
+    case 2: wta_dispatch<2>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_h_update(float *H, const float *ppart, int splits, const float *G, int k,
+                           int64_t n, float eps, hipStream_t st)
+{
+    int64_t blocks = (n + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    dim3 grid((unsigned)blocks);
+    if (k <= 8)
+        hipLaunchKernelGGL((h_update_kernel<8>), grid, dim3(256), 0, st, H, ppart, splits, G, k, n, eps);
+    else if (k <= 32)
+        hipLaunchKernelGGL((h_update_kernel<32>), grid, dim3(256), 0, st, H, ppart, splits, G, k, n, eps);
+    else
+        hipLaunchKernelGGL((h_update_kernel<64>), grid, dim3(256), 0, st, H, ppart, splits, G, k, n, eps);
+    return hipGetLastError();
+}
+
+hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
+                               hipStream_t st)
+{
+    int64_t b = (count + 255) / 256;
+    if (b > 4096) b = 4096;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b), dim3(256), 0, st, ppart, splits, count, P);
+    return hipGetLastError();
+}
+
+template <int KT>
+static void aht_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *H,
+                         const float *GH, float *W, int64_t rows, int64_t n, int k, float eps)
+{
+    constexpr int RT = kAhtRowTiles;
+    if (vec)
+        hipLaunchKernelGGL((aht_pass_kernel<KT, RT, true>), grid, dim3(512), 0, st, A, H, GH, W, rows, n, k, eps);
+    else
+        hipLaunchKernelGGL((aht_pass_kernel<KT, RT, false>), grid, dim3(512), 0, st, A, H, GH, W, rows, n, k, eps);
+}
+
+hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
+                           const float *GH, float *W, float eps, hipStream_t st)
+{
+    const int rb = 32 * kAhtRowTiles;
+    dim3 grid((unsigned)((rows + rb - 1) / rb));
+    const bool vec = vec_ok(A, n) && vec_ok(H, n);
+    switch (k_tiles(k)) {
+    case 1: aht_dispatch<1>(vec, grid, st, A, H, GH, W, rows, n, k, eps); break;
+    case 2: aht_dispatch<2>(vec, grid, st, A, H, GH, W, rows, n, k, eps); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+}  // namespace nmfmu

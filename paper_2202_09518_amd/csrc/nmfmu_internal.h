@@ -1,0 +1,62 @@
+// Internal declarations shared by the HIP translation units of libnmfmu.
+// Not part of the public ABI (that is include/nmfmu.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace nmfmu {
+
+// ---- launch geometry shared between the host scheduler and the kernels ----
+
+constexpr int kWtaWaves = 8;        // waves per workgroup in the W^T A pass
+constexpr int kWtaCols = 128;       // columns of A per workgroup in that pass
+constexpr int kAhtWaves = 8;        // waves per workgroup in the A H^T pass
+constexpr int kAhtRowTiles = 2;     // 32-row tiles per workgroup in that pass
+constexpr int kGramMaxBlocks = 64;  // partial Gram matrices before the final sum
+constexpr int kMaxKTiles = 2;       // 32-wide rank tiles: k <= 64
+
+inline int k_tiles(int k) { return (k + 31) / 32; }
+
+// Row split of the W^T A pass: number of partial k x n results, rows in each.
+int wta_splits(int64_t rows, int64_t n);
+int64_t wta_rows_per_split(int64_t rows, int splits);
+
+// ---- kernel launchers (all asynchronous on `st`; return hipGetLastError) ----
+
+// G (k x k, ld k) = X^T X for X rows x k (row-major, ld k).
+hipError_t launch_gram_w(const float *X, int64_t rows, int k, float *G, float *gpart,
+                         unsigned *counters, hipStream_t st);
+// G (k x k, ld k) = X X^T for X k x cols (row-major, ld cols).
+hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *gpart,
+                         unsigned *counters, hipStream_t st);
+// ppart[s] (+)= W[r0_s:r1_s]^T A[r0_s:r1_s] for each row split s (k x n each).
+hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
+                           float *ppart, int splits, int64_t rows_per_split, bool accumulate,
+                           hipStream_t st);
+// P[e] = sum_s ppart[s][e], e < count.
+hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
+                               hipStream_t st);
+// H <- H * (sum_s ppart[s]) / (G H + eps), in place.
+hipError_t launch_h_update(float *H, const float *ppart, int splits, const float *G, int k,
+                           int64_t n, float eps, hipStream_t st);
+// W <- W * (A H^T) / (W GH + eps), in place, for `rows` rows of A and W.
+hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
+                           const float *GH, float *W, float eps, hipStream_t st);
+
+// ---- CSR (everything in terms of Ht = H^T, n x k) ----
+hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                          int64_t m, int k, const float *Ht, const float *GH, float *W, float eps,
+                          hipStream_t st);
+// Pt (n x k) += A^T W by scattering stored entries (fp32 atomics); zero Pt first.
+hipError_t launch_wta_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                          int64_t m, int k, const float *W, float *Pt, hipStream_t st);
+// X <- X * Q / (X G + eps) row by row (X, Q rows x k; G symmetric k x k).
+hipError_t launch_row_update(float *X, const float *Q, const float *G, int64_t rows, int k,
+                             float eps, hipStream_t st);
+// out (cols x rows) = in^T.
+hipError_t launch_transpose(const float *in, int64_t rows, int64_t cols, float *out, hipStream_t st);
+hipError_t launch_fill_zero(float *p, int64_t count, hipStream_t st);
+
+}  // namespace nmfmu

@@ -1,0 +1,96 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every
+symbol the public header declares, and the pure host helpers behave."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2202_09518_amd as nmf
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for fn in os.listdir(inc):
+        if fn.endswith(".h"):
+            text = open(os.path.join(inc, fn)).read()
+            text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+            names |= set(re.findall(r"\b(nmf_\w+)\s*\(", text))
+    return sorted(names)
+
+
+def test_library_exports_every_declared_symbol():
+    L = nmf.lib()
+    decl = declared_symbols()
+    assert len(decl) >= 13
+    for name in decl:
+        assert hasattr(L, name), name
+    assert sorted(nmf.EXPORTS) == decl
+
+
+def test_binding_has_the_same_names():
+    for name in declared_symbols():
+        assert callable(getattr(nmf, name)), name
+
+
+def test_status_strings():
+    assert nmf.nmf_status_string(0) == "NMF_OK"
+    assert nmf.nmf_status_string(1) == "NMF_EINVAL"
+    assert nmf.nmf_status_string(2) == "NMF_ENOMEM"
+    assert nmf.nmf_status_string(3) == "NMF_EHIP"
+    assert nmf.nmf_status_string(4) == "NMF_EUNSUPPORTED"
+    assert nmf.nmf_status_string(99) == "NMF_UNKNOWN"
+
+
+def test_max_k_matches_header():
+    text = open(os.path.join(ROOT, "include", "nmfmu.h")).read()
+    assert int(re.search(r"#define NMF_MU_MAX_K (\d+)", text).group(1)) == nmf.NMF_MU_MAX_K
+
+
+def test_workspace_bytes():
+    wb = nmf.nmf_mu_workspace_bytes
+    assert wb(0, 0, 10, 0, 4, 0) == 0          # invalid m
+    assert wb(0, 10, 10, 0, 65, 0) == 0        # k too large
+    assert wb(7, 10, 10, 0, 4, 0) == 0         # unknown kind
+    assert wb(2, 10, 10, 0, 4, 0) == 0         # ooc needs batch_rows
+    d = wb(0, 32768, 16384, 0, 32, 0)
+    # 16 row splits of a 32 x 16384 fp32 partial plus the small Gram scratch
+    assert 16 * 32 * 16384 * 4 <= d <= 16 * 32 * 16384 * 4 + (1 << 20)
+    assert wb(1, 1000, 5000, 123, 8, 0) >= 2 * 5000 * 8 * 4
+    assert wb(2, 262144, 65536, 0, 64, 8192) == wb(0, 8192, 65536, 0, 64, 0)
+
+
+def test_argument_errors_need_no_device():
+    """Argument validation happens before any HIP call."""
+    L = nmf.lib()
+    one = ctypes.c_void_p(16)
+    null = ctypes.c_void_p(0)
+    assert L.nmf_mu_dense(null, 4, 4, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense(one, 0, 4, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense(one, 4, 4, 0, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense(one, 4, 4, 65, one, one, 1, 1e-16, null) == nmf.NMF_EUNSUPPORTED
+    assert L.nmf_mu_dense(one, 4, 4, 2, one, one, -1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense(one, 4, 4, 2, one, one, 1, -1.0, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense(one, 4, 4, 2, one, one, 1, float("nan"), null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense(one, 4, 4, 2, one, one, 1, float("inf"), null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense(one, 4, 4, 2, one, one, 0, 1e-16, null) == nmf.NMF_OK   # iters = 0
+    assert nmf.nmf_last_error() != ""
+    assert L.nmf_mu_ooc(one, 4, 4, 2, one, one, 1, 1e-16, 0, 1 << 20, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_ooc(one, 4, 4, 2, one, one, 1, 1e-16, 2, 0, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_ooc(one, 4, 4, 2, one, one, 1, 1e-16, 2, 8, null) == nmf.NMF_ENOMEM
+    assert L.nmf_mu_csr(null, one, one, 4, 4, 3, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_csr(one, null, one, 4, 4, 3, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_csr(one, one, one, 4, 4, -1, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_dense_batched(-1, one, 4, 4, one, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_set_workspace(ctypes.c_void_p(8), 4096) == nmf.NMF_EINVAL   # misaligned
+
+
+def test_missing_library_fails_loudly(monkeypatch):
+    import paper_2202_09518_amd.binding as b
+    monkeypatch.setattr(b, "_lib", None)
+    monkeypatch.setattr(b, "LIB_PATH", "/nonexistent/libnmfmu.so")
+    with pytest.raises(ImportError):
+        b.lib()
