@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the MU NMF hot path on one MI355X.
+
+Default workload (the one the headline metric is quoted on): dense fp32 A
+32768 x 16384 (2 GiB, resident in HBM), planted rank 32 with multiplicative
+U[0.95, 1.05) noise, k = 32, W and H ~ U[0, 1).  One step = one MU iteration
+(H update then W update: W^T W, W^T A, H update, H H^T, A H^T with the fused W
+update), i.e. two full reads of A.
+
+Prints ONE JSON line on stdout.  Other workloads (--workload c1|c3|c4|c5) are
+there for the measurements quoted in the design doc; they print the same kind of
+line with their own unit.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+EPS = 1e-16
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def sync_time(torch):
+    torch.cuda.synchronize()
+    return time.perf_counter()
+
+
+def cpu_baseline_dense(A_host, k, seed, iters=3):
+    """The oracle as it stands, on the host cores, on the full matrix for a
+    few iterations (its cost per iteration does not depend on the iterate)."""
+    import nmf_inputs
+    from oracle import nmf_oracle as orc
+    m, n = A_host.shape
+    W, H = nmf_inputs.init_factors(m, n, k, seed)
+    W, H = W.numpy(), H.numpy()
+    t0 = time.perf_counter()
+    orc.mu_dense(A_host, W, H, iters, EPS)
+    dt = time.perf_counter() - t0
+    return {"value": iters / dt, "unit": "iterations/s", "cores": orc.num_threads(), "kind": "oracle",
+            "sample": f"{iters} iterations of the full {m}x{n}, k={k} workload in {dt:.1f} s (float64)"}
+
+
+def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag="c2"):
+    A = nmf_inputs.dense_planted(m, n, rank, seed=1002, device="cuda")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2002, device="cuda")
+    log(f"[bench] {tag}: A {m}x{n} fp32 ({A.numel() * 4 / 2**30:.2f} GiB), k={k}")
+    if args.warmup:
+        nmf.nmf_mu_dense(A, m, n, k, W, H, args.warmup, EPS)
+    t0 = sync_time(torch)
+    nmf.nmf_mu_dense(A, m, n, k, W, H, args.steps, EPS)
+    t1 = sync_time(torch)
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    assert bool(torch.isfinite(W).all()) and bool(torch.isfinite(H).all())
+    # per-kernel times with HIP events between the launches, same launch configuration
+    names = ["gram_w", "wta_pass", "h_update", "gram_h", "aht_pass"]
+    kms = nmf.nmf_mu_dense_profile(A, m, n, k, W, H, min(args.steps, 50), EPS)
+    kern = dict(zip(names, kms))
+    log("[bench] per-kernel ms:", {a: round(b, 4) for a, b in kern.items()})
+    dom = max(("wta_pass", "aht_pass"), key=lambda x: kern[x])
+    bytes_a = m * n * 4          # one pass reads every element of A once: 4 B per element
+    ach = bytes_a / (kern[dom] * 1e-3) / 1e9
+    gbs_iter = 2 * bytes_a / (ms_step * 1e-3) / 1e9
+    out = {
+        "metric": "MU iterations/s (dense fp32, resident A)", "value": 1e3 / ms_step, "unit": "iterations/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{tag}: dense fp32 A {m}x{n} resident, planted rank {rank} x U[0.95,1.05), k={k}, "
+                               "one step = one MU iteration (2 reads of A)", "m": m, "n": n, "k": k},
+        "gbs_over_A": gbs_iter, "frac_hbm_peak_over_A": gbs_iter / HBM_PEAK_GBS,
+        "kernel_ms": kern,
+        "roofline": {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes_per_launch": bytes_a},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_dense(A.cpu().numpy(), k, seed=2002)
+    return out
+
+
+def bench_c1(args, torch, nmf, nmf_inputs):
+    m, n, k = 256, 192, 4
+    A = nmf_inputs.dense_planted(m, n, 4, seed=1001, noise="add", lo=0.0, hi=0.01).cuda()
+    W, H = (t.cuda() for t in nmf_inputs.init_factors(m, n, k, seed=2001))
+    nmf.nmf_mu_dense(A, m, n, k, W, H, max(args.warmup, 1), EPS)
+    t0 = sync_time(torch)
+    nmf.nmf_mu_dense(A, m, n, k, W, H, args.steps, EPS)
+    t1 = sync_time(torch)
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    return {"metric": "MU iterations/s (dense fp32, launch bound)", "value": 1e3 / ms_step, "unit": "iterations/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": "c1: dense 256x192, k=4"}}
+
+
+def bench_c3(args, torch, nmf, nmf_inputs):
+    m, n, k, density = 4194304, 1048576, 32, 1e-4
+    if args.small:
+        m, n = m // 16, n // 16
+        density *= 16
+    t0 = time.perf_counter()
+    rowptr, colidx, vals = nmf_inputs.csr_uniform(m, n, density, seed=1003, device="cuda")
+    nnz = int(vals.numel())
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2003, device="cuda")
+    log(f"[bench] c3: CSR {m}x{n}, nnz={nnz} ({nnz / m:.1f} per row), generated in {time.perf_counter() - t0:.1f} s")
+    nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, max(args.warmup, 1), EPS)
+    t0 = sync_time(torch)
+    nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, args.steps, EPS)
+    t1 = sync_time(torch)
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    bytes_a = 2 * (8 * nnz + 8 * (m + 1))       # both passes read values, column indices, row pointers
+    gbs = bytes_a / (ms_step * 1e-3) / 1e9
+    return {"metric": "MU iterations/s (CSR fp32)", "value": 1e3 / ms_step, "unit": "iterations/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"c3: CSR {m}x{n}, nnz={nnz}, k={k}", "nnz": nnz},
+            "gbs_over_A": gbs, "frac_hbm_peak_over_A": gbs / HBM_PEAK_GBS}
+
+
+def bench_c4(args, torch, nmf, nmf_inputs):
+    m, n, k, batch = 262144, 65536, 64, 8192
+    if args.small:
+        m //= 8
+    budget = 8 << 30
+    t0 = time.perf_counter()
+    Ah = torch.empty((m, n), dtype=torch.float32, pin_memory=True)
+    log(f"[bench] c4: pinned {m}x{n} ({m * n * 4 / 2**30:.0f} GiB) in {time.perf_counter() - t0:.1f} s")
+    t0 = time.perf_counter()
+    nmf_inputs.dense_planted(m, n, 64, seed=1004, device="cuda", out=Ah, row_block=batch)
+    torch.cuda.synchronize()
+    log(f"[bench] c4: generated in {time.perf_counter() - t0:.1f} s")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2004, device="cuda")
+    # bare copy ceiling: same chunks, same buffer, one stream
+    slot = torch.empty((batch, n), dtype=torch.float32, device="cuda")
+    nb = m // batch
+    slot.copy_(Ah[:batch], non_blocking=True)
+    t0 = sync_time(torch)
+    for b in range(nb):
+        slot.copy_(Ah[b * batch:(b + 1) * batch], non_blocking=True)
+    t1 = sync_time(torch)
+    copy_gbs = m * n * 4 / (t1 - t0) / 1e9
+    del slot
+    log(f"[bench] c4: bare pinned H2D copy {copy_gbs:.1f} GB/s")
+    iters = args.steps
+    t0 = sync_time(torch)
+    nmf.nmf_mu_ooc(Ah, m, n, k, W, H, iters, EPS, batch, budget)
+    t1 = sync_time(torch)
+    sweeps = iters + 1
+    gbs = sweeps * m * n * 4 / (t1 - t0) / 1e9
+    ms_step = (t1 - t0) * 1e3 / iters
+    return {"metric": "MU iterations/s (dense fp32, A streamed from pinned host memory)", "value": 1e3 / ms_step,
+            "unit": "iterations/s", "n_gpus": 1, "steps": iters, "warmup": 0, "ms_per_step": ms_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"c4: dense {m}x{n} in pinned host memory, {batch}-row batches, 8 GiB staging budget, "
+                                   f"k={k}, {iters} iterations = {sweeps} uploads of A"},
+            "h2d_gbs_achieved": gbs, "h2d_gbs_bare_copy": copy_gbs, "frac_of_bare_copy": gbs / copy_gbs}
+
+
+def bench_c5(args, torch, nmf, nmf_inputs):
+    m, n = 16384, 8192
+    kmin, kmax, copies = args.kmin, args.kmax, args.copies
+    base = nmf_inputs.dense_planted(m, n, 8, seed=1005, device="cuda")
+    As = [nmf_inputs.perturb(base, 3000 + p) for p in range(copies)]
+    runs_A, runs_k, Ws, Hs = [], [], [], []
+    for p in range(copies):
+        for k in range(kmin, kmax + 1):
+            W, H = nmf_inputs.init_factors(m, n, k, seed=2005 + len(runs_k), device="cuda")
+            runs_A.append(As[p]); runs_k.append(k); Ws.append(W); Hs.append(H)
+    iters = args.steps
+    nmf.nmf_mu_dense_batched(len(runs_k), runs_A, m, n, runs_k, Ws, Hs, max(args.warmup, 1), EPS)
+    t0 = sync_time(torch)
+    nmf.nmf_mu_dense_batched(len(runs_k), runs_A, m, n, runs_k, Ws, Hs, iters, EPS)
+    t1 = sync_time(torch)
+    nruns = len(runs_k)
+    per_run_500 = (t1 - t0) / nruns * (500 / iters)
+    return {"metric": "ensemble runs/s (500 MU iterations per run)", "value": 1.0 / per_run_500, "unit": "runs/s",
+            "n_gpus": 1, "steps": iters, "warmup": args.warmup, "ms_per_step": (t1 - t0) * 1e3 / iters,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"c5: dense {m}x{n}, {copies} perturbed copies x k={kmin}..{kmax} = {nruns} runs; "
+                                   f"timed {iters} iterations per run, scaled to 500"}}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--small", action="store_true", help="reduced c3/c4 sizes (debugging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--kmin", type=int, default=2)
+    ap.add_argument("--kmax", type=int, default=16)
+    ap.add_argument("--copies", type=int, default=8)
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import nmf_inputs
+    import paper_2202_09518_amd as nmf
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    nmf.lib()   # fail loudly if the HIP library is missing
+    torch.cuda.set_device(0)
+    fn = {"c1": bench_c1, "c2": bench_c2, "c3": bench_c3, "c4": bench_c4, "c5": bench_c5}[args.workload]
+    out = fn(args, torch, nmf, nmf_inputs)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -75,6 +75,17 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
                  float *W, float *H, int32_t iters, float eps, void *stream);
 
 /*
+ * nmf_mu_dense with timing: the same launches on `stream`, with a HIP event
+ * recorded between them; synchronises `stream` before returning.  On return
+ * kernel_ms[0..4] (HOST memory) hold the average milliseconds per launch of
+ * the five kernels of one iteration, in launch order: W^T W, W^T A pass,
+ * H update, H H^T, A H^T pass with the W update.  1 <= iters <= 4096.
+ */
+int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k,
+                         float *W, float *H, int32_t iters, float eps, void *stream,
+                         float *kernel_ms);
+
+/*
  * Resident sparse MU: the same iteration with A given in CSR (section 2.3
  * names the three CSR arrays: values, column indices, row pointers).
  *   rowptr  device, int64[m + 1], non-decreasing, rowptr[0] = 0, rowptr[m] = nnz

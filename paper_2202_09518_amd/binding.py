@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -49,6 +49,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_status_string.argtypes = [ctypes.c_int]
     L.nmf_last_error.restype = ctypes.c_char_p
     L.nmf_mu_dense.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp]
+    L.nmf_mu_dense_profile.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_mu_csr.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp]
     L.nmf_mu_ooc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
     L.nmf_mu_dense_batched.argtypes = [i32, vp, i64, i64, vp, vp, vp, i32, f32, vp]
@@ -99,6 +100,14 @@ def nmf_last_error() -> str:
 def nmf_mu_dense(A, m, n, k, W, H, iters, eps, stream=None) -> None:
     _check(lib().nmf_mu_dense(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
                               _dev(H, torch.float32, "H"), iters, eps, _stream(stream)))
+
+
+def nmf_mu_dense_profile(A, m, n, k, W, H, iters, eps, stream=None):
+    """Returns the five average kernel times in ms (launch order of one iteration)."""
+    ms = (ctypes.c_float * 5)()
+    _check(lib().nmf_mu_dense_profile(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
+                                      _dev(H, torch.float32, "H"), iters, eps, _stream(stream), ms))
+    return list(ms)
 
 
 def nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, stream=None) -> None:

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstring>
 #include <mutex>
+#include <vector>
 
 using namespace nmfmu;
 
@@ -118,18 +119,27 @@ int check_common(const void *a, const void *w, const void *h, int64_t m, int64_t
     return NMF_OK;
 }
 
-// One resident dense run on `st` with a workspace already carved.
+// One resident dense run on `st` with a workspace already carved.  With `ev`
+// (5 * iters + 1 events) an event is recorded before the first and after every
+// kernel, for per-kernel timing.
 int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, int iters,
-               float eps, const Common &c, float *ppart, hipStream_t st)
+               float eps, const Common &c, float *ppart, hipStream_t st,
+               hipEvent_t *ev = nullptr)
 {
     const int splits = wta_splits(m, n);
     const int64_t rps = wta_rows_per_split(m, splits);
+    if (ev) NMF_HIP(hipEventRecord(*ev++, st));
     for (int it = 0; it < iters; ++it) {
         NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         NMF_HIP(launch_wta_pass(A, m, n, k, W, ppart, splits, rps, false, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         NMF_HIP(launch_h_update(H, ppart, splits, c.gw, k, n, eps, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
     }
     return NMF_OK;
 }
@@ -235,6 +245,43 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k, float *W, floa
     const Common c = carve_common(cv, k);
     float *ppart = cv.take<float>((size_t)wta_splits(m, n) * k * n);
     return dense_body(A, m, n, k, W, H, iters, eps, c, ppart, static_cast<hipStream_t>(stream));
+}
+
+int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                         int32_t iters, float eps, void *stream, float *kernel_ms)
+{
+    if (int rc = check_common(A, W, H, m, n, k, iters, eps)) return rc;
+    if (!kernel_ms) return fail(NMF_EINVAL, "null pointer%s");
+    if (iters < 1 || iters > 4096) return fail(NMF_EINVAL, "profiled run needs 1 <= iters <= 4096%s");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(dense_bytes(m, n, k), &ws)) return rc;
+    Carve cv(ws);
+    const Common c = carve_common(cv, k);
+    float *ppart = cv.take<float>((size_t)wta_splits(m, n) * k * n);
+    std::vector<hipEvent_t> ev((size_t)iters * 5 + 1, nullptr);
+    int rc = NMF_OK;
+    for (auto &e : ev)
+        if (hipEventCreate(&e) != hipSuccess) rc = fail(NMF_EHIP, "hipEventCreate failed%s");
+    if (rc == NMF_OK) rc = dense_body(A, m, n, k, W, H, iters, eps, c, ppart, st, ev.data());
+    if (rc == NMF_OK && hipStreamSynchronize(st) != hipSuccess) rc = fail(NMF_EHIP, "hipStreamSynchronize failed%s");
+    if (rc == NMF_OK) {
+        double sum[5] = {0, 0, 0, 0, 0};
+        for (int it = 0; it < iters && rc == NMF_OK; ++it)
+            for (int j = 0; j < 5; ++j) {
+                float ms = 0.f;
+                if (hipEventElapsedTime(&ms, ev[(size_t)it * 5 + j], ev[(size_t)it * 5 + j + 1]) != hipSuccess) {
+                    rc = fail(NMF_EHIP, "hipEventElapsedTime failed%s");
+                    break;
+                }
+                sum[j] += ms;
+            }
+        for (int j = 0; j < 5; ++j) kernel_ms[j] = (float)(sum[j] / iters);
+    }
+    for (auto &e : ev)
+        if (e) (void)hipEventDestroy(e);
+    return rc;
 }
 
 int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64_t n,
