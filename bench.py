@@ -63,9 +63,10 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
     ms_step = (t1 - t0) * 1e3 / args.steps
     assert bool(torch.isfinite(W).all()) and bool(torch.isfinite(H).all())
     # per-kernel times with HIP events between the launches, same launch configuration
-    names = ["gram_w", "wta_pass", "h_update", "gram_h", "aht_pass"]
+    names = ["gram_w", "wta_pass", "h_update", "gram_h", "aht_pass", "w_update"]
     kms = nmf.nmf_mu_dense_profile(A, m, n, k, W, H, min(args.steps, 50), EPS)
-    kern = dict(zip(names, kms))
+    kern = dict(zip(names, kms[:6]))
+    log("[bench] plan:", "mirrored (A and A^T resident)" if kms[6] else "direct")
     log("[bench] per-kernel ms:", {a: round(b, 4) for a, b in kern.items()})
     dom = max(("wta_pass", "aht_pass"), key=lambda x: kern[x])
     bytes_a = m * n * 4          # one pass reads every element of A once: 4 B per element

@@ -69,7 +69,10 @@ const char *nmf_last_error(void);
  *   A      device, m x n, read-only
  *   W, H   device, in/out
  *   iters  >= 0;  eps >= 0 and finite
- * Asynchronous on `stream`.
+ * Asynchronous on `stream`.  If the workspace can hold a second copy of A the
+ * library transposes A once per call and streams A^T for the A H^T product
+ * (both passes then read memory in row order); otherwise it runs a direct
+ * A H^T kernel on A.  Both give the same iteration; low-order bits differ.
  */
 int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
                  float *W, float *H, int32_t iters, float eps, void *stream);
@@ -77,9 +80,13 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
 /*
  * nmf_mu_dense with timing: the same launches on `stream`, with a HIP event
  * recorded between them; synchronises `stream` before returning.  On return
- * kernel_ms[0..4] (HOST memory) hold the average milliseconds per launch of
- * the five kernels of one iteration, in launch order: W^T W, W^T A pass,
- * H update, H H^T, A H^T pass with the W update.  1 <= iters <= 4096.
+ * kernel_ms[0..5] (HOST memory, 7 floats) hold the average milliseconds per
+ * launch of the kernels of one iteration, in launch order:
+ *   [0] W^T W   [1] W^T A pass   [2] H update   [3] H H^T
+ *   [4] A H^T pass (on the mirrored copy A^T, or the direct kernel with the W
+ *       update fused)   [5] W update (0 for the direct kernel)
+ * and kernel_ms[6] is 1 if the mirrored plan ran (see nmf_mu_workspace_bytes),
+ * else 0.  1 <= iters <= 4096.
  */
 int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k,
                          float *W, float *H, int32_t iters, float eps, void *stream,
@@ -134,9 +141,11 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
                          int32_t iters, float eps, void *stream);
 
 /*
- * Workspace the given problem needs, in bytes (kind: 0 dense, 1 csr, 2 ooc
- * [excluding the staging slots], 3 batched with k = largest rank).  0 on
- * invalid arguments.
+ * Workspace the given problem needs, in bytes.  kind: 0 dense (fast plan: the
+ * library keeps a transposed copy of A, so this is about m*n*4 bytes plus the
+ * partial sums), 4 dense (small plan: partial sums only; used automatically
+ * when the fast plan's workspace cannot be had), 1 csr, 2 ooc (excluding the
+ * staging slots), 3 batched with k = largest rank.  0 on invalid arguments.
  */
 size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz,
                               int32_t k, int64_t batch_rows);

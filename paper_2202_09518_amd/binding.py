@@ -103,8 +103,8 @@ def nmf_mu_dense(A, m, n, k, W, H, iters, eps, stream=None) -> None:
 
 
 def nmf_mu_dense_profile(A, m, n, k, W, H, iters, eps, stream=None):
-    """Returns the five average kernel times in ms (launch order of one iteration)."""
-    ms = (ctypes.c_float * 5)()
+    """Returns [six average kernel times in ms (launch order of one iteration), mirrored flag]."""
+    ms = (ctypes.c_float * 7)()
     _check(lib().nmf_mu_dense_profile(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
                                       _dev(H, torch.float32, "H"), iters, eps, _stream(stream), ms))
     return list(ms)

@@ -119,34 +119,109 @@ int check_common(const void *a, const void *w, const void *h, int64_t m, int64_t
     return NMF_OK;
 }
 
-// One resident dense run on `st` with a workspace already carved.  With `ev`
-// (5 * iters + 1 events) an event is recorded before the first and after every
-// kernel, for per-kernel timing.
+// Plan of one resident dense run.  The fast plan ("mirrored") keeps A^T, W^T
+// and H^T next to A, W, H, so that the A H^T product becomes the same
+// row-streaming contraction as W^T A (on A^T with H^T: the two updates are
+// transposes of each other) and its update the same finisher on W^T.  It costs
+// one extra copy of A in the workspace; without it the direct A H^T kernel runs.
+struct DensePlan {
+    bool mirrored;
+    Common c;
+    float *ppart;              // row-split partials of either pass
+    float *At, *Wt, *Ht;       // mirrored only
+    int s1, s2;                // row splits of the pass over A / over A^T
+    int64_t rps1, rps2;
+};
+
+size_t dense_bytes(int64_t m, int64_t n, int k, bool mirrored)
+{
+    const size_t p1 = (size_t)wta_splits(m, n) * k * n, p2 = (size_t)wta_splits(n, m) * k * m;
+    size_t b = common_bytes(k) + align_up(((mirrored && p2 > p1) ? p2 : p1) * sizeof(float));
+    if (mirrored)
+        b += align_up((size_t)m * n * sizeof(float)) + align_up((size_t)k * m * sizeof(float)) +
+             align_up((size_t)n * k * sizeof(float));
+    return b;
+}
+
+DensePlan carve_dense(void *ws, int64_t m, int64_t n, int k, bool mirrored)
+{
+    Carve cv(ws);
+    DensePlan p;
+    p.mirrored = mirrored;
+    p.c = carve_common(cv, k);
+    p.s1 = wta_splits(m, n);
+    p.rps1 = wta_rows_per_split(m, p.s1);
+    p.s2 = wta_splits(n, m);
+    p.rps2 = wta_rows_per_split(n, p.s2);
+    const size_t p1 = (size_t)p.s1 * k * n, p2 = (size_t)p.s2 * k * m;
+    p.ppart = cv.take<float>((mirrored && p2 > p1) ? p2 : p1);
+    p.At = p.Wt = p.Ht = nullptr;
+    if (mirrored) {
+        p.At = cv.take<float>((size_t)m * n);
+        p.Wt = cv.take<float>((size_t)k * m);
+        p.Ht = cv.take<float>((size_t)n * k);
+    }
+    return p;
+}
+
+// Workspace for a dense run: the mirrored plan if it can be had, else the small one.
+int dense_workspace(int64_t m, int64_t n, int k, void **ws, bool *mirrored)
+{
+    const size_t big = dense_bytes(m, n, k, true), small = dense_bytes(m, n, k, false);
+    if (g.ws && g.ws_bytes >= big) {
+        *ws = g.ws;
+        *mirrored = true;
+        return NMF_OK;
+    }
+    if (g.ws_owned && ensure_workspace(big, ws) == NMF_OK) {
+        *mirrored = true;
+        return NMF_OK;
+    }
+    (void)hipGetLastError();
+    *mirrored = false;
+    return ensure_workspace(small, ws);
+}
+
+constexpr int kDenseKernels = 6;
+
+// One resident dense run on `st`.  With `ev` (kDenseKernels * iters + 1 events)
+// an event is recorded before the first kernel of the loop and after every
+// kernel, for per-kernel timing; slots of kernels a plan does not use collapse
+// to zero duration.  `a_is_mirrored`: At already holds this A's transpose.
 int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, int iters,
-               float eps, const Common &c, float *ppart, hipStream_t st,
+               float eps, const DensePlan &p, hipStream_t st, bool a_is_mirrored = false,
                hipEvent_t *ev = nullptr)
 {
-    const int splits = wta_splits(m, n);
-    const int64_t rps = wta_rows_per_split(m, splits);
+    const Common &c = p.c;
+    if (p.mirrored) {
+        if (!a_is_mirrored) NMF_HIP(launch_transpose(A, m, n, p.At, st));
+        NMF_HIP(launch_transpose(W, m, k, p.Wt, st));
+        NMF_HIP(launch_transpose(H, k, n, p.Ht, st));
+    }
     if (ev) NMF_HIP(hipEventRecord(*ev++, st));
     for (int it = 0; it < iters; ++it) {
         NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        NMF_HIP(launch_wta_pass(A, m, n, k, W, ppart, splits, rps, false, st));
+        NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, p.s1, p.rps1, false, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        NMF_HIP(launch_h_update(H, ppart, splits, c.gw, k, n, eps, st));
+        NMF_HIP(launch_h_update(H, p.Ht, p.ppart, p.s1, c.gw, k, n, eps, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
-        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
-        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        if (p.mirrored) {
+            NMF_HIP(launch_gram_w(p.Ht, n, k, c.gh, c.gpart, c.counters, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.ppart, p.s2, p.rps2, false, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_h_update(p.Wt, W, p.ppart, p.s2, c.gh, k, m, eps, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        } else {
+            NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        }
     }
     return NMF_OK;
-}
-
-size_t dense_bytes(int64_t m, int64_t n, int k)
-{
-    return common_bytes(k) + align_up((size_t)wta_splits(m, n) * k * n * sizeof(float));
 }
 
 size_t csr_bytes(int64_t n, int k) { return common_bytes(k) + 2 * align_up((size_t)n * k * sizeof(float)); }
@@ -176,11 +251,12 @@ size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz, int32
     if (m < 1 || n < 1 || k < 1 || k > NMF_MU_MAX_K) return 0;
     switch (kind) {
     case 0:
-    case 3: return dense_bytes(m, n, k);
+    case 3: return dense_bytes(m, n, k, true);
+    case 4: return dense_bytes(m, n, k, false);
     case 1: return csr_bytes(n, k);
     case 2:
         if (batch_rows < 1) return 0;
-        return dense_bytes(batch_rows < m ? batch_rows : m, n, k);
+        return dense_bytes(batch_rows < m ? batch_rows : m, n, k, false);
     default: return 0;
     }
 }
@@ -240,11 +316,10 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k, float *W, floa
     if (iters == 0) return NMF_OK;
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
-    if (int rc = ensure_workspace(dense_bytes(m, n, k), &ws)) return rc;
-    Carve cv(ws);
-    const Common c = carve_common(cv, k);
-    float *ppart = cv.take<float>((size_t)wta_splits(m, n) * k * n);
-    return dense_body(A, m, n, k, W, H, iters, eps, c, ppart, static_cast<hipStream_t>(stream));
+    bool mirrored = false;
+    if (int rc = dense_workspace(m, n, k, &ws, &mirrored)) return rc;
+    const DensePlan p = carve_dense(ws, m, n, k, mirrored);
+    return dense_body(A, m, n, k, W, H, iters, eps, p, static_cast<hipStream_t>(stream));
 }
 
 int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
@@ -256,28 +331,29 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float 
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
-    if (int rc = ensure_workspace(dense_bytes(m, n, k), &ws)) return rc;
-    Carve cv(ws);
-    const Common c = carve_common(cv, k);
-    float *ppart = cv.take<float>((size_t)wta_splits(m, n) * k * n);
-    std::vector<hipEvent_t> ev((size_t)iters * 5 + 1, nullptr);
+    bool mirrored = false;
+    if (int rc = dense_workspace(m, n, k, &ws, &mirrored)) return rc;
+    const DensePlan p = carve_dense(ws, m, n, k, mirrored);
+    constexpr int NK = kDenseKernels;
+    std::vector<hipEvent_t> ev((size_t)iters * NK + 1, nullptr);
     int rc = NMF_OK;
     for (auto &e : ev)
         if (hipEventCreate(&e) != hipSuccess) rc = fail(NMF_EHIP, "hipEventCreate failed%s");
-    if (rc == NMF_OK) rc = dense_body(A, m, n, k, W, H, iters, eps, c, ppart, st, ev.data());
+    if (rc == NMF_OK) rc = dense_body(A, m, n, k, W, H, iters, eps, p, st, false, ev.data());
     if (rc == NMF_OK && hipStreamSynchronize(st) != hipSuccess) rc = fail(NMF_EHIP, "hipStreamSynchronize failed%s");
     if (rc == NMF_OK) {
-        double sum[5] = {0, 0, 0, 0, 0};
+        double sum[NK] = {0, 0, 0, 0, 0, 0};
         for (int it = 0; it < iters && rc == NMF_OK; ++it)
-            for (int j = 0; j < 5; ++j) {
+            for (int j = 0; j < NK; ++j) {
                 float ms = 0.f;
-                if (hipEventElapsedTime(&ms, ev[(size_t)it * 5 + j], ev[(size_t)it * 5 + j + 1]) != hipSuccess) {
+                if (hipEventElapsedTime(&ms, ev[(size_t)it * NK + j], ev[(size_t)it * NK + j + 1]) != hipSuccess) {
                     rc = fail(NMF_EHIP, "hipEventElapsedTime failed%s");
                     break;
                 }
                 sum[j] += ms;
             }
-        for (int j = 0; j < 5; ++j) kernel_ms[j] = (float)(sum[j] / iters);
+        for (int j = 0; j < NK; ++j) kernel_ms[j] = (float)(sum[j] / iters);
+        kernel_ms[NK] = mirrored ? 1.f : 0.f;
     }
     for (auto &e : ev)
         if (e) (void)hipEventDestroy(e);
@@ -297,13 +373,15 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
     if (iters == 0 || n_runs == 0) return NMF_OK;
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
-    if (int rc = ensure_workspace(dense_bytes(m, n, kmax), &ws)) return rc;
+    bool mirrored = false;
+    if (int rc = dense_workspace(m, n, kmax, &ws, &mirrored)) return rc;
+    // Carve once with the largest rank so that A^T sits at one address for all
+    // runs: consecutive runs on the same A then share its transpose.
+    const DensePlan p = carve_dense(ws, m, n, kmax, mirrored);
     for (int r = 0; r < n_runs; ++r) {
-        Carve cv(ws);
-        const Common c = carve_common(cv, k[r]);
-        float *ppart = cv.take<float>((size_t)wta_splits(m, n) * k[r] * n);
-        if (int rc = dense_body(A[r], m, n, k[r], W[r], H[r], iters, eps, c, ppart,
-                                static_cast<hipStream_t>(stream)))
+        const bool same_a = r > 0 && A[r] == A[r - 1];
+        if (int rc = dense_body(A[r], m, n, k[r], W[r], H[r], iters, eps, p,
+                                static_cast<hipStream_t>(stream), same_a))
             return rc;
     }
     return NMF_OK;
@@ -326,7 +404,7 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
 
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
-    if (int rc = ensure_workspace(dense_bytes(batch_rows, n, k), &ws)) return rc;
+    if (int rc = ensure_workspace(dense_bytes(batch_rows, n, k, false), &ws)) return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
     const int splits = wta_splits(batch_rows, n);
@@ -376,7 +454,7 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
         }
         if (s < iters) {
             NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
-            NMF_HIP(launch_h_update(H, ppart, splits, c.gw, k, n, eps, st));
+            NMF_HIP(launch_h_update(H, nullptr, ppart, splits, c.gw, k, n, eps, st));
             NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
         }
     }
@@ -435,7 +513,7 @@ int nmf_wta_dense(const float *A, int64_t m, int64_t n, int32_t k, const float *
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
-    if (int rc = ensure_workspace(dense_bytes(m, n, k), &ws)) return rc;
+    if (int rc = ensure_workspace(dense_bytes(m, n, k, false), &ws)) return rc;
     Carve cv(ws);
     carve_common(cv, k);
     const int splits = wta_splits(m, n);
@@ -455,7 +533,7 @@ int nmf_h_update(float *H, const float *P, const float *G, int32_t k, int64_t n,
     if (int rc = ensure_workspace(common_bytes(k), &ws)) return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
-    NMF_HIP(launch_h_update(H, P, 1, G, k, n, eps, st));
+    NMF_HIP(launch_h_update(H, nullptr, P, 1, G, k, n, eps, st));
     if (GH) NMF_HIP(launch_gram_h(H, k, n, GH, c.gpart, c.counters, st));
     return NMF_OK;
 }

@@ -45,7 +45,15 @@ __device__ __forceinline__ f32x4 load4(const float *__restrict__ X, int64_t ncol
 {
     f32x4 v = {0.f, 0.f, 0.f, 0.f};
     if (VEC) {
-        if (ok && col < ncols) v = *reinterpret_cast<const f32x4 *>(X + row * ncols + col);
+        // Branch free: lanes outside the matrix read element (0, 0) and discard
+        // it, so the loads of a stage stay in one basic block and the waits on
+        // them can be counted exactly (needed for the software prefetch).
+        const bool in = ok && col < ncols;
+        const f32x4 t = *reinterpret_cast<const f32x4 *>(X + (in ? row * ncols + col : 0));
+        v.x = in ? t.x : 0.f;
+        v.y = in ? t.y : 0.f;
+        v.z = in ? t.z : 0.f;
+        v.w = in ? t.w : 0.f;
     } else {
         if (ok) {
             const float *p = X + row * ncols + col;
@@ -66,11 +74,11 @@ __device__ __forceinline__ f32x4 load4(const float *__restrict__ X, int64_t ncol
 // last adds the partials in block order (deterministic) and stores G.
 // ---------------------------------------------------------------------------
 template <int MODE, bool VEC>
-__global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ X, int64_t len, int k,
+__global__ __launch_bounds__(512) void gram_kernel(const float *__restrict__ X, int64_t len, int k,
                                                    float *__restrict__ G, float *gpart,
                                                    unsigned *counters)
 {
-    constexpr int NW = 4;
+    constexpr int NW = 8;
     __shared__ float red[1024];
     __shared__ unsigned ticket_s;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
@@ -80,28 +88,45 @@ __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ X, 
     const int c1 = 32 * t1 + jj, c2 = 32 * t2 + jj;
     const int64_t gw = (int64_t)blockIdx.x * NW + w, tw = (int64_t)gridDim.x * NW;
 
+    // Operands of several steps are fetched before the first multiply so that
+    // the loads overlap; all loads are branch free (out-of-range lanes read
+    // element 0 and discard it).
     f32x16 acc = {0};
     if (MODE == 0) {
+        constexpr int UN = 8;
         const int64_t npairs = (len + 1) >> 1;
-        for (int64_t p = gw; p < npairs; p += tw) {
-            const int64_t row = 2 * p + half;
-            const bool ok = row < len;
-            const float a = (ok && c1 < k) ? X[row * k + c1] : 0.f;
-            const float b = (ok && c2 < k) ? X[row * k + c2] : 0.f;
-            acc = mfma32(a, b, acc);
+        for (int64_t p = gw; p < npairs; p += tw * UN) {
+            float a[UN], b[UN];
+#pragma unroll
+            for (int u = 0; u < UN; ++u) {
+                const int64_t row = 2 * (p + u * tw) + half;
+                const bool in1 = row < len && c1 < k, in2 = row < len && c2 < k;
+                const float va = X[in1 ? row * k + c1 : 0], vb = X[in2 ? row * k + c2 : 0];
+                a[u] = in1 ? va : 0.f;
+                b[u] = in2 ? vb : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u) acc = mfma32(a[u], b[u], acc);
         }
     } else {
+        constexpr int UN = 4;
         const int64_t ngroups = (len + 7) >> 3;
-        for (int64_t g = gw; g < ngroups; g += tw) {
-            const int64_t col = 8 * g + 4 * half;
-            const f32x4 a = load4<VEC>(X, len, c1, col, c1 < k);
-            const f32x4 b = load4<VEC>(X, len, c2, col, c2 < k);
+        for (int64_t g = gw; g < ngroups; g += tw * UN) {
+            f32x4 a[UN], b[UN];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) acc = mfma32(a[q], b[q], acc);
+            for (int u = 0; u < UN; ++u) {
+                const int64_t col = 8 * (g + u * tw) + 4 * half;
+                a[u] = load4<VEC>(X, len, c1, col, c1 < k);
+                b[u] = load4<VEC>(X, len, c2, col, c2 < k);
+            }
+#pragma unroll
+            for (int u = 0; u < UN; ++u)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) acc = mfma32(a[u][q], b[u][q], acc);
         }
     }
 
-    // Sum the four waves in wave order.
+    // Sum the waves in wave order.
     for (int ww = 0; ww < NW; ++ww) {
         if (w == ww) {
 #pragma unroll
@@ -114,19 +139,30 @@ __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ X, 
     }
     const int ntiles = gridDim.y;
     float *mine = gpart + ((int64_t)blockIdx.x * ntiles + blockIdx.y) * 1024;
-    for (int e = tid; e < 1024; e += 256) mine[e] = red[e];
+    for (int e = tid; e < 1024; e += 64 * NW) mine[e] = red[e];
     __threadfence();
     __syncthreads();
     if (tid == 0) ticket_s = atomicAdd(&counters[blockIdx.y], 1u);
     __syncthreads();
     if (ticket_s != gridDim.x - 1) return;
+    // Last block to arrive: every partial tile is visible after this fence.
+    // Loads are issued in groups of eight so that they overlap; the sum runs
+    // in block order whatever the arrival order was.
     __threadfence();
-    for (int e = tid; e < 1024; e += 256) {
+    const volatile float *vp = gpart;
+    for (int e = tid; e < 1024; e += 64 * NW) {
         float s = 0.f;
-        for (unsigned b = 0; b < gridDim.x; ++b) {
-            const float *src = gpart + ((int64_t)b * ntiles + blockIdx.y) * 1024 + e;
-            s += __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const int64_t stride = (int64_t)ntiles * 1024;
+        const int64_t base = (int64_t)blockIdx.y * 1024 + e;
+        unsigned b = 0;
+        for (; b + 8 <= gridDim.x; b += 8) {
+            float t[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) t[u] = vp[base + (b + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) s += t[u];
         }
+        for (; b < gridDim.x; ++b) s += vp[base + b * stride];
         const int v = e >> 6, l = e & 63;
         const int r1 = 32 * t1 + acc_row(v, l >> 5), r2 = 32 * t2 + (l & 31);
         if (r1 < k && r2 < k) G[r1 * k + r2] = s;
@@ -135,17 +171,20 @@ __global__ __launch_bounds__(256) void gram_kernel(const float *__restrict__ X, 
 }
 
 // ---------------------------------------------------------------------------
-// W^T A pass.  Workgroup = 8 waves on one 128-column slab of A and one row
-// split; wave w takes row pairs w, w+8, ... of the split.  Per row pair a lane
+// W^T A pass.  Workgroup = 4 waves on one 128-column slab of A and one row
+// split; wave w takes row pairs w, w+4, ... of the split.  Per row pair a lane
 // loads four consecutive columns (one 16-byte load, 512 contiguous bytes per
 // row and wave) and one element of each W row; column tile q of the wave
 // therefore holds columns j0 + 4 jj + q.  MFMA roles: A_op = W rows (factor
 // index across lanes), B_op = A elements (column across lanes), reduction
-// over the two rows.  The eight waves are summed through LDS in wave order and
-// the slab is written (or added) to the split's partial result.
+// over the two rows.  The waves are summed through LDS in wave order and the
+// slab is written (or added) to the split's partial result.
+// Registers are capped (OCC waves per SIMD) so that several workgroups share a
+// compute unit: one group's reduction epilogue then hides behind the others'
+// streaming, and enough loads are in flight to cover the HBM latency.
 // ---------------------------------------------------------------------------
-template <int KT, int U, bool VEC>
-__global__ __launch_bounds__(512) void wta_pass_kernel(const float *__restrict__ A,
+template <int KT, int U, int OCC, bool VEC>
+__global__ __launch_bounds__(64 * kWtaWaves, OCC) void wta_pass_kernel(const float *__restrict__ A,
                                                        const float *__restrict__ W,
                                                        float *__restrict__ ppart, int64_t rows,
                                                        int64_t n, int k, int64_t rps,
@@ -180,7 +219,9 @@ __global__ __launch_bounds__(512) void wta_pass_kernel(const float *__restrict__
 #pragma unroll
             for (int t = 0; t < KT; ++t) {
                 const int c = 32 * t + jj;
-                s.wv[u][t] = (ok && c < k) ? W[row * k + c] : 0.f;
+                const bool in = ok && c < k;
+                const float wv = W[in ? row * k + c : 0];
+                s.wv[u][t] = in ? wv : 0.f;
             }
         }
     };
@@ -216,7 +257,7 @@ __global__ __launch_bounds__(512) void wta_pass_kernel(const float *__restrict__
         __syncthreads();
     }
     float *dst = ppart + (int64_t)blockIdx.y * k * n;
-    for (int e = tid; e < k * kWtaCols; e += 512) {
+    for (int e = tid; e < k * kWtaCols; e += 64 * NW) {
         const int c = e >> 7, x = e & 127;
         const int64_t cj = j0 + x;
         if (cj < n) {
@@ -229,32 +270,68 @@ __global__ __launch_bounds__(512) void wta_pass_kernel(const float *__restrict__
 }
 
 // ---------------------------------------------------------------------------
-// H update: one thread per column j.  The old column is held in registers, so
-// the column can be overwritten factor by factor.
+// H update.  A block covers 64 columns; thread (column j, group g of 4) holds
+// the old column of H in registers and produces the factor indices c = g, g+4,
+// g+8, ... of the new column:  H[c][j] * WTA[c][j] / (sum_d WTW[c][d] H[d][j] + eps).
+// Every element is written by the one thread that computed it after a block
+// barrier, so all reads of the old column come first.  If Ht is given, the
+// transposed factor (n x k) is written as well, staged through LDS so that the
+// block stores one contiguous run of 64 k floats.
+// The same kernel performs the W update on transposed data: with H := W^T
+// (k x m), partials of (A H^T)^T and G := H H^T it is the W-update line.
 // ---------------------------------------------------------------------------
 template <int KP>
-__global__ __launch_bounds__(256) void h_update_kernel(float *H, const float *__restrict__ ppart,
+__global__ __launch_bounds__(256) void h_update_kernel(float *H, float *Ht,
+                                                       const float *__restrict__ ppart,
                                                        int splits, const float *__restrict__ G,
                                                        int k, int64_t n, float eps)
 {
-    for (int64_t j = (int64_t)blockIdx.x * 256 + threadIdx.x; j < n; j += (int64_t)gridDim.x * 256) {
+    __shared__ float Gs[KP * (KP + 1)];
+    __shared__ float Ts[64 * (KP + 1)];
+    for (int e = threadIdx.x; e < KP * KP; e += 256) {
+        const int c = e / KP, d = e % KP;
+        Gs[c * (KP + 1) + d] = (c < k && d < k) ? G[c * k + d] : 0.f;
+    }
+    __syncthreads();
+    const int jl = threadIdx.x & 63, grp = threadIdx.x >> 6;
+    const int64_t nchunks = (n + 63) >> 6;
+    for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
+        const int64_t j = ch * 64 + jl;
+        const bool okj = j < n;
         float h[KP];
 #pragma unroll
-        for (int d = 0; d < KP; ++d) h[d] = (d < k) ? H[(int64_t)d * n + j] : 0.f;
-        for (int c = 0; c < k; ++c) {
+        for (int d = 0; d < KP; ++d) {
+            const bool in = okj && d < k;
+            const float v = H[in ? (int64_t)d * n + j : 0];
+            h[d] = in ? v : 0.f;
+        }
+        __syncthreads();   // every old value of this chunk is in registers
+        for (int c = grp; c < k; c += 4) {
             float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+            const float *g = Gs + c * (KP + 1);
 #pragma unroll
             for (int d = 0; d < KP; d += 4) {
-                d0 += ((d + 0 < k) ? G[c * k + d + 0] : 0.f) * h[d + 0];
-                d1 += ((d + 1 < k) ? G[c * k + d + 1] : 0.f) * h[d + 1];
-                d2 += ((d + 2 < k) ? G[c * k + d + 2] : 0.f) * h[d + 2];
-                d3 += ((d + 3 < k) ? G[c * k + d + 3] : 0.f) * h[d + 3];
+                d0 += g[d + 0] * h[d + 0];
+                d1 += g[d + 1] * h[d + 1];
+                d2 += g[d + 2] * h[d + 2];
+                d3 += g[d + 3] * h[d + 3];
             }
             const float den = ((d0 + d1) + (d2 + d3)) + eps;
-            float p = 0.f;
-            for (int s = 0; s < splits; ++s) p += ppart[((int64_t)s * k + c) * n + j];
-            const int64_t at = (int64_t)c * n + j;
-            H[at] = H[at] * p / den;
+            if (okj) {
+                float p = 0.f;
+                for (int s = 0; s < splits; ++s) p += ppart[((int64_t)s * k + c) * n + j];
+                const int64_t at = (int64_t)c * n + j;
+                const float nv = H[at] * p / den;
+                H[at] = nv;
+                Ts[jl * (KP + 1) + c] = nv;
+            }
+        }
+        if (Ht) {
+            __syncthreads();
+            for (int e = threadIdx.x; e < 64 * k; e += 256) {
+                const int jj = e / k, c = e % k;
+                if (ch * 64 + jj < n) Ht[(ch * 64 + jj) * k + c] = Ts[jj * (KP + 1) + c];
+            }
         }
     }
 }
@@ -423,7 +500,7 @@ hipError_t launch_gram_w(const float *X, int64_t rows, int k, float *G, float *g
 {
     const int kt = k_tiles(k);
     dim3 grid(gram_blocks(rows, 512), kt * kt);
-    hipLaunchKernelGGL((gram_kernel<0, false>), grid, dim3(256), 0, st, X, rows, k, G, gpart, counters);
+    hipLaunchKernelGGL((gram_kernel<0, false>), grid, dim3(512), 0, st, X, rows, k, G, gpart, counters);
     return hipGetLastError();
 }
 
@@ -431,11 +508,11 @@ hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *g
                          unsigned *counters, hipStream_t st)
 {
     const int kt = k_tiles(k);
-    dim3 grid(gram_blocks(cols, 1024), kt * kt);
+    dim3 grid(gram_blocks(cols, 512), kt * kt);
     if (vec_ok(X, cols))
-        hipLaunchKernelGGL((gram_kernel<1, true>), grid, dim3(256), 0, st, X, cols, k, G, gpart, counters);
+        hipLaunchKernelGGL((gram_kernel<1, true>), grid, dim3(512), 0, st, X, cols, k, G, gpart, counters);
     else
-        hipLaunchKernelGGL((gram_kernel<1, false>), grid, dim3(256), 0, st, X, cols, k, G, gpart, counters);
+        hipLaunchKernelGGL((gram_kernel<1, false>), grid, dim3(512), 0, st, X, cols, k, G, gpart, counters);
     return hipGetLastError();
 }
 
@@ -443,11 +520,12 @@ template <int KT>
 static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *W,
                          float *ppart, int64_t rows, int64_t n, int k, int64_t rps, int acc)
 {
-    constexpr int U = 4;
+    constexpr int U = 2, OCC = (KT == 1) ? 4 : 2;
+    const dim3 block(64 * kWtaWaves);
     if (vec)
-        hipLaunchKernelGGL((wta_pass_kernel<KT, U, true>), grid, dim3(512), 0, st, A, W, ppart, rows, n, k, rps, acc);
+        hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, true>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);
     else
-        hipLaunchKernelGGL((wta_pass_kernel<KT, U, false>), grid, dim3(512), 0, st, A, W, ppart, rows, n, k, rps, acc);
+        hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, false>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);
 }
 
 hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
@@ -464,18 +542,18 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
     return hipGetLastError();
 }
 
-hipError_t launch_h_update(float *H, const float *ppart, int splits, const float *G, int k,
-                           int64_t n, float eps, hipStream_t st)
+hipError_t launch_h_update(float *H, float *Ht, const float *ppart, int splits, const float *G,
+                           int k, int64_t n, float eps, hipStream_t st)
 {
-    int64_t blocks = (n + 255) / 256;
+    int64_t blocks = (n + 63) / 64;
     if (blocks > 4096) blocks = 4096;
     dim3 grid((unsigned)blocks);
     if (k <= 8)
-        hipLaunchKernelGGL((h_update_kernel<8>), grid, dim3(256), 0, st, H, ppart, splits, G, k, n, eps);
+        hipLaunchKernelGGL((h_update_kernel<8>), grid, dim3(256), 0, st, H, Ht, ppart, splits, G, k, n, eps);
     else if (k <= 32)
-        hipLaunchKernelGGL((h_update_kernel<32>), grid, dim3(256), 0, st, H, ppart, splits, G, k, n, eps);
+        hipLaunchKernelGGL((h_update_kernel<32>), grid, dim3(256), 0, st, H, Ht, ppart, splits, G, k, n, eps);
     else
-        hipLaunchKernelGGL((h_update_kernel<64>), grid, dim3(256), 0, st, H, ppart, splits, G, k, n, eps);
+        hipLaunchKernelGGL((h_update_kernel<64>), grid, dim3(256), 0, st, H, Ht, ppart, splits, G, k, n, eps);
     return hipGetLastError();
 }
 

@@ -10,7 +10,7 @@ namespace nmfmu {
 
 // ---- launch geometry shared between the host scheduler and the kernels ----
 
-constexpr int kWtaWaves = 8;        // waves per workgroup in the W^T A pass
+constexpr int kWtaWaves = 4;        // waves per workgroup in the W^T A pass
 constexpr int kWtaCols = 128;       // columns of A per workgroup in that pass
 constexpr int kAhtWaves = 8;        // waves per workgroup in the A H^T pass
 constexpr int kAhtRowTiles = 2;     // 32-row tiles per workgroup in that pass
@@ -38,9 +38,9 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
 // P[e] = sum_s ppart[s][e], e < count.
 hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
                                hipStream_t st);
-// H <- H * (sum_s ppart[s]) / (G H + eps), in place.
-hipError_t launch_h_update(float *H, const float *ppart, int splits, const float *G, int k,
-                           int64_t n, float eps, hipStream_t st);
+// H <- H * (sum_s ppart[s]) / (G H + eps), in place; if Ht != nullptr also Ht (n x k) = new H^T.
+hipError_t launch_h_update(float *H, float *Ht, const float *ppart, int splits, const float *G,
+                           int k, int64_t n, float eps, hipStream_t st);
 // W <- W * (A H^T) / (W GH + eps), in place, for `rows` rows of A and W.
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
                            const float *GH, float *W, float eps, hipStream_t st);

@@ -56,11 +56,14 @@ def test_workspace_bytes():
     assert wb(0, 10, 10, 0, 65, 0) == 0        # k too large
     assert wb(7, 10, 10, 0, 4, 0) == 0         # unknown kind
     assert wb(2, 10, 10, 0, 4, 0) == 0         # ooc needs batch_rows
-    d = wb(0, 32768, 16384, 0, 32, 0)
-    # 16 row splits of a 32 x 16384 fp32 partial plus the small Gram scratch
-    assert 16 * 32 * 16384 * 4 <= d <= 16 * 32 * 16384 * 4 + (1 << 20)
+    d = wb(4, 32768, 16384, 0, 32, 0)
+    # small plan: 16 row splits of a 32 x 16384 fp32 partial plus the Gram scratch
+    assert 16 * 32 * 16384 * 4 <= d <= 16 * 32 * 16384 * 4 + (2 << 20)
+    # fast plan: additionally A^T, W^T and H^T
+    extra = (32768 * 16384 + 32 * 32768 + 16384 * 32) * 4
+    assert d + extra <= wb(0, 32768, 16384, 0, 32, 0) <= d + extra + (1 << 20)
     assert wb(1, 1000, 5000, 123, 8, 0) >= 2 * 5000 * 8 * 4
-    assert wb(2, 262144, 65536, 0, 64, 8192) == wb(0, 8192, 65536, 0, 64, 0)
+    assert wb(2, 262144, 65536, 0, 64, 8192) == wb(4, 8192, 65536, 0, 64, 0)
 
 
 def test_argument_errors_need_no_device():

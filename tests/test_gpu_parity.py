@@ -205,14 +205,44 @@ def test_ooc_matches_oracle(m, n, k, batch, slots, iters):
     check(host(Wd), host(Hd), Wr, Hr, TOL1 * iters)
 
 
-def test_ooc_equals_dense_bitwise_when_one_batch():
+def test_ooc_equals_small_plan_dense_bitwise_when_one_batch():
+    """With one batch the out-of-memory path launches the same kernels as the
+    resident path without the transposed copy of A (forced here by a caller
+    workspace too small for that copy)."""
     A, W, H = case(640, 512, 32, 80)
-    Wg, Hg = run_dense(A, W, H, 4)
-    Ah = torch.from_numpy(A).pin_memory()
-    Wd, Hd = dev(W), dev(H)
-    nmf.nmf_mu_ooc(Ah, 640, 512, 32, Wd, Hd, 4, EPS, 640, 1 << 30)
-    np.testing.assert_array_equal(host(Wd), Wg)
-    np.testing.assert_array_equal(host(Hd), Hg)
+    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, 640, 512, 0, 32, 0), dtype=torch.uint8, device="cuda")
+    nmf.nmf_mu_set_workspace(buf)
+    try:
+        Wg, Hg = run_dense(A, W, H, 4)
+        Ah = torch.from_numpy(A).pin_memory()
+        Wd, Hd = dev(W), dev(H)
+        nmf.nmf_mu_ooc(Ah, 640, 512, 32, Wd, Hd, 4, EPS, 640, 1 << 30)
+        np.testing.assert_array_equal(host(Wd), Wg)
+        np.testing.assert_array_equal(host(Hd), Hg)
+    finally:
+        nmf.nmf_mu_set_workspace(None)
+    Wr, Hr = orc.mu_dense(A, W, H, 4, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 4 * TOL1)
+
+
+@pytest.mark.parametrize("m,n,k", SHAPES)
+def test_small_plan_dense_one_iteration(m, n, k):
+    """The direct A H^T kernel (no transposed copy of A) against the oracle."""
+    A, W, H = case(m, n, k, 31)
+    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, m, n, 0, k, 0), dtype=torch.uint8, device="cuda")
+    nmf.nmf_mu_set_workspace(buf)
+    try:
+        Wg, Hg = run_dense(A, W, H, 1)
+    finally:
+        nmf.nmf_mu_set_workspace(None)
+    Wr, Hr = orc.mu_dense(A, W, H, 1, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, TOL1)
+
+
+def test_profile_entry_reports_plan_and_times():
+    A, W, H = case(512, 384, 8, 33)
+    ms = nmf.nmf_mu_dense_profile(dev(A), 512, 384, 8, dev(W), dev(H), 3, EPS)
+    assert len(ms) == 7 and ms[6] == 1.0 and all(x >= 0 for x in ms[:6]) and ms[1] > 0 and ms[4] > 0
 
 
 def test_ooc_pageable_host_memory_and_config1():
