@@ -24,6 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
+# HBM bytes per launch of the streaming pass kernel on the default workload, from the
+# FETCH_SIZE / WRITE_SIZE counters in profiles/dense_c2_hbm_traffic_pmc.txt (scaled by the
+# plain-copy calibration stated there); only reported when that workload is the one timed.
+C2_PASS_TRAFFIC_BYTES = (1060998.6 * 2.0 + 32768.0) * 1024.0
 EPS = 1e-16
 
 
@@ -55,6 +59,13 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
     A = nmf_inputs.dense_planted(m, n, rank, seed=1002, device="cuda")
     W, H = nmf_inputs.init_factors(m, n, k, seed=2002, device="cuda")
     log(f"[bench] {tag}: A {m}x{n} fp32 ({A.numel() * 4 / 2**30:.2f} GiB), k={k}")
+    if args.calibrate:
+        # a plain device copy of known size (reads and writes A.numel()*4 bytes), for scaling
+        # the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run
+        B = torch.empty_like(A)
+        B.copy_(A)
+        torch.cuda.synchronize()
+        del B
     if args.warmup:
         nmf.nmf_mu_dense(A, m, n, k, W, H, args.warmup, EPS)
     t0 = sync_time(torch)
@@ -81,7 +92,8 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
         "gbs_over_A": gbs_iter, "frac_hbm_peak_over_A": gbs_iter / HBM_PEAK_GBS,
         "kernel_ms": kern,
         "roofline": {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": ach / HBM_PEAK_GBS, "traffic": None,
+                     "frac": ach / HBM_PEAK_GBS,
+                     "traffic": C2_PASS_TRAFFIC_BYTES if (m, n, k, bool(kms[6])) == (32768, 16384, 32, True) else None,
                      "algorithmic_bytes_per_launch": bytes_a},
     }
     if not args.no_cpu_baseline:
@@ -199,6 +211,7 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--small", action="store_true", help="reduced c3/c4 sizes (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate", action="store_true", help="also run one plain device copy of A (counter scaling)")
     ap.add_argument("--kmin", type=int, default=2)
     ap.add_argument("--kmax", type=int, default=16)
     ap.add_argument("--copies", type=int, default=8)
