@@ -247,3 +247,53 @@ def rel_fro(X, Xref) -> float:
     Xref = np.asarray(Xref, dtype=np.float64)
     den = np.linalg.norm(Xref)
     return float(np.linalg.norm(X - Xref) / den) if den > 0 else float(np.linalg.norm(X))
+
+
+# ---- the same iteration with library matrix products as the steps -----------
+#
+# Cross-checks of the loop oracle, not replacements for it: the six lines of
+# Algorithm 3 taken literally as numpy / scipy.sparse float64 products.  Dense
+# A is widened to double one row block at a time (the co-linear row batches of
+# Algorithm 5), which only bounds memory: every product is still a plain sum
+# over all rows.  (They are slower than the C loops at the shapes of interest:
+# thin products are a poor fit for the BLAS.)
+
+def mu_dense_blas(A, W0, H0, iters, eps, row_block=8192):
+    """`iters` MU iterations (H then W) with float64 library matmuls."""
+    m, n = A.shape
+    W = _f64(W0)
+    H = _f64(H0)
+    eps = float(eps)
+    for _ in range(int(iters)):
+        WTW = W.T @ W
+        WTA = np.zeros((W.shape[1], n))
+        for i0 in range(0, m, row_block):
+            Ab = np.asarray(A[i0:i0 + row_block], dtype=np.float64)
+            WTA += W[i0:i0 + row_block].T @ Ab
+        H = H * WTA / (WTW @ H + eps)
+        HHT = H @ H.T
+        for i0 in range(0, m, row_block):
+            Ab = np.asarray(A[i0:i0 + row_block], dtype=np.float64)
+            Wb = W[i0:i0 + row_block]
+            W[i0:i0 + row_block] = Wb * (Ab @ H.T) / (Wb @ HHT + eps)
+    return W, H
+
+
+def mu_csr_scipy(rowptr, colidx, vals, m, n, W0, H0, iters, eps):
+    """The CSR iteration with scipy.sparse float64 products (repeated entries
+    of the CSR arrays add up, as in the loop oracle)."""
+    import scipy.sparse as sp
+    A = sp.csr_matrix((np.asarray(vals, dtype=np.float64), np.asarray(colidx), np.asarray(rowptr)),
+                      shape=(m, n))
+    At = A.T.tocsr()
+    W = _f64(W0)
+    H = _f64(H0)
+    eps = float(eps)
+    for _ in range(int(iters)):
+        WTW = W.T @ W
+        WTA = np.ascontiguousarray((At @ W).T)
+        H = H * WTA / (WTW @ H + eps)
+        HHT = H @ H.T
+        AHT = A @ np.ascontiguousarray(H.T)
+        W = W * AHT / (W @ HHT + eps)
+    return W, H

@@ -1,0 +1,108 @@
+"""Parity at the full sizes of the benchmark configurations, through the same
+entry points and launch configurations that bench.py times.
+
+Where one oracle iteration at full size takes seconds, whole results are
+compared; for the 64 GiB out-of-memory configuration the H update is compared
+in full and the W update on sampled rows (a row of the W update needs only
+that row of A once the new H is known, so the oracle computes the sampled rows
+one by one from its own new H).
+"""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+import nmf_inputs
+import paper_2202_09518_amd as nmf
+from oracle import nmf_oracle as orc
+
+pytestmark = [pytest.mark.gpu, pytest.mark.timeout(900)]
+
+EPS = 1e-16
+EPSD = float(np.float32(EPS))
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def errs(Wd, Hd, Wr, Hr):
+    torch.cuda.synchronize()
+    return orc.rel_fro(Wd.cpu().numpy(), Wr), orc.rel_fro(Hd.cpu().numpy(), Hr)
+
+
+def test_config2_full_size_1_and_100_iterations():
+    m, n, k = 32768, 16384, 32
+    A = nmf_inputs.dense_planted(m, n, 32, seed=1002, device="cuda")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2002, device="cuda")
+    Ah, W0, H0 = A.cpu().numpy(), W.cpu().numpy(), H.cpu().numpy()
+    W1, H1 = W.clone(), H.clone()
+    nmf.nmf_mu_dense(A, m, n, k, W1, H1, 1, EPS)
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 1, EPSD)
+    ew, eh = errs(W1, H1, Wr, Hr)
+    say(f"config 2 full size, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 1e-5
+    nmf.nmf_mu_dense(A, m, n, k, W, H, 100, EPS)
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 100, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    say(f"config 2 full size, 100 iterations: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 1e-3
+    assert bool((W >= 0).all()) and bool((H >= 0).all())
+
+
+def test_config3_full_size_one_iteration():
+    m, n, k = 4194304, 1048576, 32
+    rowptr, colidx, vals = nmf_inputs.csr_uniform(m, n, 1e-4, seed=1003, device="cuda")
+    nnz = int(vals.numel())
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2003, device="cuda")
+    rp0, ci0, va0 = rowptr.clone(), colidx.clone(), vals.clone()
+    W0, H0 = W.cpu().numpy(), H.cpu().numpy()
+    nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, 1, EPS)
+    torch.cuda.synchronize()
+    assert torch.equal(rowptr, rp0) and torch.equal(colidx, ci0) and torch.equal(vals, va0)
+    del rp0, ci0, va0
+    say(f"config 3: nnz = {nnz}; running the oracle (about a minute)")
+    Wr, Hr = orc.mu_csr(rowptr.cpu().numpy(), colidx.cpu().numpy(), vals.cpu().numpy(), m, n, W0, H0, 1, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    say(f"config 3 full size, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 1e-5
+
+
+def test_config4_full_size_one_iteration_h_full_w_sampled():
+    m, n, k, batch = 262144, 65536, 64, 8192
+    Ah = torch.empty((m, n), dtype=torch.float32, pin_memory=True)
+    nmf_inputs.dense_planted(m, n, 64, seed=1004, device="cuda", out=Ah, row_block=batch)
+    torch.cuda.synchronize()
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2004, device="cuda")
+    W0, H0 = W.cpu().numpy(), H.cpu().numpy()
+    nmf.nmf_mu_ooc(Ah, m, n, k, W, H, 1, EPS, batch, 8 << 30)
+    torch.cuda.synchronize()
+    nmf.nmf_mu_release()          # give the 6 GiB of staging back
+    An = Ah.numpy()
+    say("config 4: oracle W^T A over 64 GiB (about a minute)")
+    Hr = orc.h_update(H0, orc.wta_dense(An, W0), orc.gram_w(W0), EPSD)
+    eh = orc.rel_fro(H.cpu().numpy(), Hr)
+    rows = np.sort(np.random.default_rng(4).choice(m, 192, replace=False))
+    rows[0], rows[-1] = 0, m - 1
+    Wr = orc.w_update(W0[rows], orc.aht_dense(An[rows], Hr), orc.gram_h(Hr), EPSD)
+    ew = orc.rel_fro(W.cpu().numpy()[rows], Wr)
+    say(f"config 4 full size, 1 iteration: rel err H {eh:.2e} (all), W {ew:.2e} (192 sampled rows)")
+    assert max(ew, eh) < 1e-5
+    assert bool(torch.isfinite(W).all()) and bool((W >= 0).all())
+
+
+@pytest.mark.parametrize("k", [2, 16])
+def test_config5_shape_one_copy_1_and_100_iterations(k):
+    m, n = 16384, 8192
+    base = nmf_inputs.dense_planted(m, n, 8, seed=1005, device="cuda")
+    A = nmf_inputs.perturb(base, 3000)
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2005 + k, device="cuda")
+    Ah, W0, H0 = A.cpu().numpy(), W.cpu().numpy(), H.cpu().numpy()
+    for iters in (1, 100):
+        Wd, Hd = W.clone(), H.clone()
+        nmf.nmf_mu_dense_batched(1, [A], m, n, [k], [Wd], [Hd], iters, EPS)
+        Wr, Hr = orc.mu_dense(Ah, W0, H0, iters, EPSD)
+        ew, eh = errs(Wd, Hd, Wr, Hr)
+        say(f"config 5 shape, k={k}, {iters} iterations: rel err W {ew:.2e} H {eh:.2e}")
+        assert max(ew, eh) < (1e-5 if iters == 1 else 1e-3)

@@ -442,3 +442,28 @@ def test_reproducible_run_to_run():
     W2, H2 = orc.mu_dense(A, W, H, 5, EPS)
     np.testing.assert_array_equal(W1, W2)
     np.testing.assert_array_equal(H1, H2)
+
+
+# --- the loop oracle against the same lines written as library products ---------------------
+
+@pytest.mark.parametrize("m,n,k,block", [(40, 33, 4, 7), (129, 65, 9, 64), (64, 200, 17, 1000)])
+def test_blas_variant_equals_loop_oracle(m, n, k, block):
+    A, W, H = small_case(m, n, k, 141)
+    W1, H1 = orc.mu_dense(A, W, H, 6, EPS)
+    W2, H2 = orc.mu_dense_blas(A, W, H, 6, EPS, row_block=block)
+    np.testing.assert_allclose(W2, W1, rtol=1e-11)
+    np.testing.assert_allclose(H2, H1, rtol=1e-11)
+
+
+def test_scipy_variant_equals_loop_oracle():
+    r = rng(151)
+    m, n, k = 60, 45, 5
+    A = r.random((m, n), dtype=np.float32)
+    A[r.random((m, n)) < 0.7] = 0.0
+    A[7, :] = 0.0
+    rowptr, colidx, vals = _scrambled_csr(A, 151)
+    W = r.random((m, k)); H = r.random((k, n))
+    W1, H1 = orc.mu_csr(rowptr, colidx, vals, m, n, W, H, 5, EPS)
+    W2, H2 = orc.mu_csr_scipy(rowptr, colidx, vals, m, n, W, H, 5, EPS)
+    np.testing.assert_allclose(W2, W1, rtol=1e-11, atol=1e-300)
+    np.testing.assert_allclose(H2, H1, rtol=1e-11, atol=1e-300)
