@@ -64,6 +64,7 @@ struct Carve {
 struct Common {
     unsigned *counters;
     float *gw, *gh, *gpart;
+    float *gwp, *ghp;   // partial Gram tiles handed from one finisher to the next
 };
 
 Common carve_common(Carve &c, int k)
@@ -74,6 +75,8 @@ Common carve_common(Carve &c, int k)
     r.gh = c.take<float>((size_t)k * k);
     const int kt = k_tiles(k);
     r.gpart = c.take<float>((size_t)kGramMaxBlocks * kt * kt * 1024);
+    r.gwp = c.take<float>((size_t)kFinMaxBlocks * kt * kt * 1024);
+    r.ghp = c.take<float>((size_t)kFinMaxBlocks * kt * kt * 1024);
     return r;
 }
 
@@ -198,28 +201,41 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
         NMF_HIP(launch_transpose(W, m, k, p.Wt, st));
         NMF_HIP(launch_transpose(H, k, n, p.Ht, st));
     }
+    if (p.mirrored) {
+        // W^T W of the initial W as partial tiles, from the finisher in its Gram-only
+        // mode (same bits as the tiles a preceding W update would have left, so that
+        // a run split into two calls equals one call); afterwards every finisher
+        // hands the Gram tiles of its new factor to the next one.
+        NMF_HIP(launch_factor_update(p.Wt, nullptr, nullptr, 0, nullptr, nullptr, 0, c.gwp, k, m, eps, st));
+        const int nbw = factor_update_blocks(m), nbh = factor_update_blocks(n);
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        for (int it = 0; it < iters; ++it) {
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, p.s1, p.rps1, false, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, p.s1, nullptr, c.gwp, nbw, c.ghp, k, n, eps, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.ppart, p.s2, p.rps2, false, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, p.s2, nullptr, c.ghp, nbh, c.gwp, k, m, eps, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        }
+        return NMF_OK;
+    }
     if (ev) NMF_HIP(hipEventRecord(*ev++, st));
     for (int it = 0; it < iters; ++it) {
         NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, p.s1, p.rps1, false, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        NMF_HIP(launch_h_update(H, p.Ht, p.ppart, p.s1, c.gw, k, n, eps, st));
+        NMF_HIP(launch_factor_update(H, nullptr, p.ppart, p.s1, c.gw, nullptr, 0, nullptr, k, n, eps, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        if (p.mirrored) {
-            NMF_HIP(launch_gram_w(p.Ht, n, k, c.gh, c.gpart, c.counters, st));
-            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.ppart, p.s2, p.rps2, false, st));
-            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_h_update(p.Wt, W, p.ppart, p.s2, c.gh, k, m, eps, st));
-            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        } else {
-            NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
-            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
-            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        }
+        NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
     }
     return NMF_OK;
 }
@@ -454,7 +470,7 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
         }
         if (s < iters) {
             NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
-            NMF_HIP(launch_h_update(H, nullptr, ppart, splits, c.gw, k, n, eps, st));
+            NMF_HIP(launch_factor_update(H, nullptr, ppart, splits, c.gw, nullptr, 0, nullptr, k, n, eps, st));
             NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
         }
     }
@@ -533,7 +549,7 @@ int nmf_h_update(float *H, const float *P, const float *G, int32_t k, int64_t n,
     if (int rc = ensure_workspace(common_bytes(k), &ws)) return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
-    NMF_HIP(launch_h_update(H, nullptr, P, 1, G, k, n, eps, st));
+    NMF_HIP(launch_factor_update(H, nullptr, P, 1, G, nullptr, 0, nullptr, k, n, eps, st));
     if (GH) NMF_HIP(launch_gram_h(H, k, n, GH, c.gpart, c.counters, st));
     return NMF_OK;
 }

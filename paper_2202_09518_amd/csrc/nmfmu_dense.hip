@@ -140,6 +140,7 @@ __global__ __launch_bounds__(512) void gram_kernel(const float *__restrict__ X, 
     const int ntiles = gridDim.y;
     float *mine = gpart + ((int64_t)blockIdx.x * ntiles + blockIdx.y) * 1024;
     for (int e = tid; e < 1024; e += 64 * NW) mine[e] = red[e];
+    if (G == nullptr) return;   // the consumer sums the partial tiles itself
     __threadfence();
     __syncthreads();
     if (tid == 0) ticket_s = atomicAdd(&counters[blockIdx.y], 1u);
@@ -270,70 +271,170 @@ __global__ __launch_bounds__(64 * kWtaWaves, OCC) void wta_pass_kernel(const flo
 }
 
 // ---------------------------------------------------------------------------
-// H update.  A block covers 64 columns; thread (column j, group g of 4) holds
-// the old column of H in registers and produces the factor indices c = g, g+4,
-// g+8, ... of the new column:  H[c][j] * WTA[c][j] / (sum_d WTW[c][d] H[d][j] + eps).
-// Every element is written by the one thread that computed it after a block
-// barrier, so all reads of the old column come first.  If Ht is given, the
-// transposed factor (n x k) is written as well, staged through LDS so that the
-// block stores one contiguous run of 64 k floats.
-// The same kernel performs the W update on transposed data: with H := W^T
-// (k x m), partials of (A H^T)^T and G := H H^T it is the W-update line.
+// Factor update ("finisher").  For X (k x len), partials of its numerator and
+// the Gram matrix G of the other factor:
+//     X[c][j] <- X[c][j] * (sum_s part[s][c][j]) / (sum_d G[c][d] X[d][j] + eps).
+// With X = H, part = W^T A, G = W^T W this is the H-update line of Algorithm 3;
+// with X = W^T, part = (A H^T)^T, G = H H^T it is the W-update line.
+// A block covers 64 columns at a time; thread (column j, group g of 8) holds
+// the old column in registers and produces factor indices c = g, g+8, ...
+// Every element is written by the thread that computed it, after a block
+// barrier that follows all reads of the old column.
+// G comes either complete (Gfull, ld k) or as `nbin` partial 32 x 32 tiles in
+// accumulator layout (gin), which every block sums in block order while
+// staging G into LDS.  Optional outputs: Xt (len x k), staged through LDS so a
+// block stores one contiguous run of 64 k floats, and gout: this block's
+// partial Gram tiles of the NEW X (X X^T), computed from the LDS copy with the
+// same register as both MFMA operands; the next finisher consumes them, so no
+// separate Gram kernel and no cross-block reduction are needed.  With
+// part == nullptr (and splits == 0) nothing is updated and only gout is produced.
 // ---------------------------------------------------------------------------
 template <int KP>
-__global__ __launch_bounds__(256) void h_update_kernel(float *H, float *Ht,
-                                                       const float *__restrict__ ppart,
-                                                       int splits, const float *__restrict__ G,
-                                                       int k, int64_t n, float eps)
+__global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
+                                                            const float *__restrict__ part,
+                                                            int splits,
+                                                            const float *__restrict__ Gfull,
+                                                            const float *__restrict__ gin, int nbin,
+                                                            float *__restrict__ gout, int k,
+                                                            int64_t len, float eps)
 {
-    __shared__ float Gs[KP * (KP + 1)];
-    __shared__ float Ts[64 * (KP + 1)];
-    for (int e = threadIdx.x; e < KP * KP; e += 256) {
+    constexpr int NW = 8, KT = KP / 32 > 0 ? KP / 32 : 1, NC = (KP + 7) / 8, LD = KP + 1;
+    constexpr int LDT = 32 * KT + 1;   // the Gram tiles read 32 factor indices per tile
+    __shared__ float Gs[KP * LD];
+    __shared__ float Ts[64 * LDT];
+    __shared__ float red[1024];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int kt = (k + 31) >> 5;
+
+    for (int e = tid; e < KP * KP; e += 64 * NW) {
         const int c = e / KP, d = e % KP;
-        Gs[c * (KP + 1) + d] = (c < k && d < k) ? G[c * k + d] : 0.f;
+        float v = 0.f;
+        if (c < k && d < k) {
+            if (Gfull) {
+                v = Gfull[c * k + d];
+            } else {
+                const int r1 = c & 31, r2 = d & 31;
+                const int pos = ((r1 & 3) + 4 * (r1 >> 3)) * 64 + r2 + 32 * ((r1 >> 2) & 1);
+                const float *src = gin + (int64_t)((c >> 5) * kt + (d >> 5)) * 1024 + pos;
+                const int64_t stride = (int64_t)kt * kt * 1024;
+                int b = 0;
+                for (; b + 8 <= nbin; b += 8) {
+                    float t[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) t[u] = src[(b + u) * stride];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) v += t[u];
+                }
+                for (; b < nbin; ++b) v += src[b * stride];
+            }
+        }
+        Gs[c * LD + d] = v;
     }
     __syncthreads();
-    const int jl = threadIdx.x & 63, grp = threadIdx.x >> 6;
-    const int64_t nchunks = (n + 63) >> 6;
+
+    f32x16 acc[KT][KT];
+#pragma unroll
+    for (int a = 0; a < KT; ++a)
+#pragma unroll
+        for (int b = 0; b < KT; ++b) acc[a][b] = f32x16{0};
+
+    const int jl = lane, grp = w;
+    const int64_t nchunks = (len + 63) >> 6;
     for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
         const int64_t j = ch * 64 + jl;
-        const bool okj = j < n;
+        const bool okj = j < len;
         float h[KP];
 #pragma unroll
         for (int d = 0; d < KP; ++d) {
             const bool in = okj && d < k;
-            const float v = H[in ? (int64_t)d * n + j : 0];
+            const float v = X[in ? (int64_t)d * len + j : 0];
             h[d] = in ? v : 0.f;
         }
-        __syncthreads();   // every old value of this chunk is in registers
-        for (int c = grp; c < k; c += 4) {
-            float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
-            const float *g = Gs + c * (KP + 1);
+        float p[NC];
 #pragma unroll
-            for (int d = 0; d < KP; d += 4) {
-                d0 += g[d + 0] * h[d + 0];
-                d1 += g[d + 1] * h[d + 1];
-                d2 += g[d + 2] * h[d + 2];
-                d3 += g[d + 3] * h[d + 3];
-            }
-            const float den = ((d0 + d1) + (d2 + d3)) + eps;
-            if (okj) {
-                float p = 0.f;
-                for (int s = 0; s < splits; ++s) p += ppart[((int64_t)s * k + c) * n + j];
-                const int64_t at = (int64_t)c * n + j;
-                const float nv = H[at] * p / den;
-                H[at] = nv;
-                Ts[jl * (KP + 1) + c] = nv;
+        for (int ci = 0; ci < NC; ++ci) p[ci] = 0.f;
+        for (int s = 0; s < splits; ++s) {
+#pragma unroll
+            for (int ci = 0; ci < NC; ++ci) {
+                const int c = grp + 8 * ci;
+                const bool in = okj && c < k;
+                const float v = part[in ? ((int64_t)s * k + c) * len + j : 0];   // splits == 0 without part
+                p[ci] += in ? v : 0.f;
             }
         }
-        if (Ht) {
-            __syncthreads();
-            for (int e = threadIdx.x; e < 64 * k; e += 256) {
+        __syncthreads();   // every old value of this chunk is in registers; Ts is free
+#pragma unroll
+        for (int ci = 0; ci < NC; ++ci) {
+            const int c = grp + 8 * ci;
+            if (c < k && part == nullptr) {
+                // Gram-only mode: no update, the tiles of the current X are produced
+                // with exactly the summation order an updating launch would use.
+                const float v = X[okj ? (int64_t)c * len + j : 0];
+                Ts[jl * LDT + c] = okj ? v : 0.f;
+            } else if (c < k) {
+                float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+                const float *g = Gs + c * LD;
+#pragma unroll
+                for (int d = 0; d < KP; d += 4) {
+                    d0 += g[d + 0] * h[d + 0];
+                    d1 += g[d + 1] * h[d + 1];
+                    d2 += g[d + 2] * h[d + 2];
+                    d3 += g[d + 3] * h[d + 3];
+                }
+                const float den = ((d0 + d1) + (d2 + d3)) + eps;
+                float nv = 0.f;
+                if (okj) {
+                    const int64_t at = (int64_t)c * len + j;
+                    nv = X[at] * p[ci] / den;
+                    X[at] = nv;
+                }
+                Ts[jl * LDT + c] = nv;   // columns past the end contribute zeros
+            }
+        }
+        __syncthreads();
+        if (Xt) {
+            for (int e = tid; e < 64 * k; e += 64 * NW) {
                 const int jj = e / k, c = e % k;
-                if (ch * 64 + jj < n) Ht[(ch * 64 + jj) * k + c] = Ts[jj * (KP + 1) + c];
+                if (ch * 64 + jj < len) Xt[(ch * 64 + jj) * k + c] = Ts[jj * LDT + c];
+            }
+        }
+        if (gout) {
+            const int jj = lane & 31, half = lane >> 5;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int row = 2 * (w + NW * q) + half;   // column pair of this chunk
+#pragma unroll
+                for (int a = 0; a < KT; ++a) {
+                    const float va = Ts[row * LDT + 32 * a + jj];
+#pragma unroll
+                    for (int b = 0; b < KT; ++b) {
+                        const float vb = Ts[row * LDT + 32 * b + jj];
+                        acc[a][b] = mfma32(va, vb, acc[a][b]);
+                    }
+                }
             }
         }
     }
+    if (!gout) return;
+    // Rows and columns of a tile at factor indices >= k hold whatever LDS held;
+    // consumers never read them.
+    for (int a = 0; a < KT; ++a)
+        for (int b = 0; b < KT; ++b) {
+            if (a >= kt || b >= kt) continue;
+            for (int ww = 0; ww < NW; ++ww) {
+                if (w == ww) {
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        if (ww == 0) red[v * 64 + lane] = acc[a][b][v];
+                        else red[v * 64 + lane] += acc[a][b][v];
+                    }
+                }
+                __syncthreads();
+            }
+            float *dst = gout + ((int64_t)blockIdx.x * kt * kt + a * kt + b) * 1024;
+            for (int e = tid; e < 1024; e += 64 * NW) dst[e] = red[e];
+            __syncthreads();
+        }
 }
 
 // ---------------------------------------------------------------------------
@@ -520,7 +621,7 @@ template <int KT>
 static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *W,
                          float *ppart, int64_t rows, int64_t n, int k, int64_t rps, int acc)
 {
-    constexpr int U = 2, OCC = (KT == 1) ? 4 : 2;
+    constexpr int U = (KT == 1) ? 3 : 2, OCC = (KT == 1) ? 4 : 2;
     const dim3 block(64 * kWtaWaves);
     if (vec)
         hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, true>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);
@@ -542,18 +643,29 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
     return hipGetLastError();
 }
 
-hipError_t launch_h_update(float *H, float *Ht, const float *ppart, int splits, const float *G,
-                           int k, int64_t n, float eps, hipStream_t st)
+int gram_w_blocks(int64_t rows) { return gram_blocks(rows, 512); }
+
+int factor_update_blocks(int64_t len)
 {
-    int64_t blocks = (n + 63) / 64;
-    if (blocks > 4096) blocks = 4096;
-    dim3 grid((unsigned)blocks);
+    int64_t b = (len + 63) / 64;
+    if (b > kFinMaxBlocks) b = kFinMaxBlocks;
+    return (int)b;
+}
+
+hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
+                                const float *Gfull, const float *gin, int nbin, float *gout, int k,
+                                int64_t len, float eps, hipStream_t st)
+{
+    // Without Gram output there is no reason to cap the grid: one block per chunk.
+    int64_t blocks = gout ? factor_update_blocks(len) : (len + 63) / 64;
+    if (blocks > 65535) blocks = 65535;
+    const dim3 grid((unsigned)blocks), block(512);
     if (k <= 8)
-        hipLaunchKernelGGL((h_update_kernel<8>), grid, dim3(256), 0, st, H, Ht, ppart, splits, G, k, n, eps);
+        hipLaunchKernelGGL((factor_update_kernel<8>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps);
     else if (k <= 32)
-        hipLaunchKernelGGL((h_update_kernel<32>), grid, dim3(256), 0, st, H, Ht, ppart, splits, G, k, n, eps);
+        hipLaunchKernelGGL((factor_update_kernel<32>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps);
     else
-        hipLaunchKernelGGL((h_update_kernel<64>), grid, dim3(256), 0, st, H, Ht, ppart, splits, G, k, n, eps);
+        hipLaunchKernelGGL((factor_update_kernel<64>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps);
     return hipGetLastError();
 }
 

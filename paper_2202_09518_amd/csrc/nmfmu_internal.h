@@ -15,6 +15,7 @@ constexpr int kWtaCols = 128;       // columns of A per workgroup in that pass
 constexpr int kAhtWaves = 8;        // waves per workgroup in the A H^T pass
 constexpr int kAhtRowTiles = 2;     // 32-row tiles per workgroup in that pass
 constexpr int kGramMaxBlocks = 64;  // partial Gram matrices before the final sum
+constexpr int kFinMaxBlocks = 128;  // finisher blocks when they also emit Gram partials
 constexpr int kMaxKTiles = 2;       // 32-wide rank tiles: k <= 64
 
 inline int k_tiles(int k) { return (k + 31) / 32; }
@@ -38,9 +39,16 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
 // P[e] = sum_s ppart[s][e], e < count.
 hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
                                hipStream_t st);
-// H <- H * (sum_s ppart[s]) / (G H + eps), in place; if Ht != nullptr also Ht (n x k) = new H^T.
-hipError_t launch_h_update(float *H, float *Ht, const float *ppart, int splits, const float *G,
-                           int k, int64_t n, float eps, hipStream_t st);
+// X (k x len) <- X * (sum_s part[s]) / (G X + eps), in place.  G is given complete (Gfull, ld k)
+// or as nbin partial tiles (gin).  Optional: Xt (len x k) = new X^T; gout = partial Gram tiles
+// of the new X, one set per block (factor_update_blocks(len) blocks).
+hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
+                                const float *Gfull, const float *gin, int nbin, float *gout, int k,
+                                int64_t len, float eps, hipStream_t st);
+int factor_update_blocks(int64_t len);
+// Blocks (= partial tile sets) launch_gram_w uses for `rows` rows; with G == nullptr it only
+// writes the partial tiles to gpart.
+int gram_w_blocks(int64_t rows);
 // W <- W * (A H^T) / (W GH + eps), in place, for `rows` rows of A and W.
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
                            const float *GH, float *W, float eps, hipStream_t st);
