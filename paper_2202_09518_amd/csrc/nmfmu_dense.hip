@@ -353,12 +353,30 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
         float p[NC];
 #pragma unroll
         for (int ci = 0; ci < NC; ++ci) p[ci] = 0.f;
-        for (int s = 0; s < splits; ++s) {
+        // Partial sums in split order; four splits' loads are issued together.
+        int s = 0;
+        for (; s + 4 <= splits; s += 4) {
+            float t[4][NC];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int ci = 0; ci < NC; ++ci) {
+                    const int c = grp + 8 * ci;
+                    const bool in = okj && c < k;
+                    const float v = part[in ? ((int64_t)(s + u) * k + c) * len + j : 0];
+                    t[u][ci] = in ? v : 0.f;
+                }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+#pragma unroll
+                for (int ci = 0; ci < NC; ++ci) p[ci] += t[u][ci];
+        }
+        for (; s < splits; ++s) {
 #pragma unroll
             for (int ci = 0; ci < NC; ++ci) {
                 const int c = grp + 8 * ci;
                 const bool in = okj && c < k;
-                const float v = part[in ? ((int64_t)s * k + c) * len + j : 0];   // splits == 0 without part
+                const float v = part[in ? ((int64_t)s * k + c) * len + j : 0];
                 p[ci] += in ? v : 0.f;
             }
         }
