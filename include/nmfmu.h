@@ -99,10 +99,13 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k,
  *   colidx  device, int32[nnz], each in [0, n); order within a row is free and
  *           repeated (row, column) pairs add up
  *   vals    device, float[nnz]
- * The CSR arrays are read-only and are not reordered or copied; the only
- * derived structure is a transposed copy of H (n x k) in the workspace.
- * Sums over stored entries use fp32 atomics for W^T A, so low-order bits may
- * differ from run to run.  Asynchronous on `stream`.
+ * The CSR arrays are read-only.  The library builds, once per call and in its
+ * workspace, a column-ordered copy of the matrix (8 bytes per stored entry plus
+ * 8 (n + 1) bytes) and a transposed copy of H; both products then gather rows
+ * of a factor per stored entry, without atomics, so results are reproducible
+ * from run to run.  Needs nnz < 2^31 and m < 2^31.  The build sorts with
+ * transient scratch memory (about 24 bytes per stored entry) and synchronises
+ * `stream` once; the iterations are then enqueued asynchronously.
  */
 int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                int64_t m, int64_t n, int64_t nnz, int32_t k,
@@ -161,6 +164,14 @@ int nmf_mu_set_workspace(void *dev_ptr, size_t bytes);
 int nmf_mu_release(void);
 
 /* ---- single steps, exposed for testing and profiling (same conventions) ---- */
+
+/* Column-ordered copy of a CSR matrix, the structure nmf_mu_csr derives for its
+ * W^T A product: colptr int64[n + 1], rowidx int32[nnz], cvals float[nnz] (all
+ * device, caller-allocated).  Entries of a column keep the order in which the
+ * CSR arrays store them (stable).  Synchronises `stream`. */
+int nmf_csr_to_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                   int64_t m, int64_t n, int64_t nnz,
+                   int64_t *colptr, int32_t *rowidx, float *cvals, void *stream);
 
 /* G (k x k, ld k) = W^T W.  Algorithm 3, formation of WTW. */
 int nmf_gram_w(const float *W, int64_t m, int32_t k, float *G, void *stream);

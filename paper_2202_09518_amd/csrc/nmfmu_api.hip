@@ -240,7 +240,38 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
     return NMF_OK;
 }
 
-size_t csr_bytes(int64_t n, int k) { return common_bytes(k) + 2 * align_up((size_t)n * k * sizeof(float)); }
+size_t csr_bytes(int64_t n, int64_t nnz, int k)
+{
+    return common_bytes(k) + align_up((size_t)n * k * sizeof(float)) +      // Ht
+           align_up((size_t)(n + 1) * sizeof(int64_t)) +                      // column pointers
+           align_up((size_t)nnz * sizeof(int32_t)) + align_up((size_t)nnz * sizeof(float));
+}
+
+// Column-ordered copy of a CSR matrix; the sort scratch is transient (allocated
+// and freed here, which synchronises with `st`).
+int build_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
+              int64_t n, int64_t nnz, int64_t *colptr, int32_t *rowidx, float *cvals, hipStream_t st)
+{
+    const size_t idx_bytes = align_up((size_t)nnz * sizeof(int32_t));
+    const size_t pl_bytes = align_up((size_t)nnz * sizeof(uint64_t));
+    const size_t temp_bytes = nnz ? csc_sort_temp_bytes(nnz, n) : 0;
+    void *scratch = nullptr;
+    if (nnz) {
+        hipError_t e = hipMalloc(&scratch, idx_bytes + 2 * pl_bytes + align_up(temp_bytes) + kAlign);
+        if (e != hipSuccess) return fail(NMF_ENOMEM, "hipMalloc(sort scratch): %s", hipGetErrorString(e));
+    }
+    char *sp = static_cast<char *>(scratch);
+    hipError_t e = launch_csc_build(rowptr, colidx, vals, m, n, nnz,
+                                    reinterpret_cast<int32_t *>(sp + 2 * pl_bytes),
+                                    reinterpret_cast<uint64_t *>(sp),
+                                    reinterpret_cast<uint64_t *>(sp + pl_bytes),
+                                    sp + 2 * pl_bytes + idx_bytes, temp_bytes, colptr, rowidx, cvals, st);
+    hipError_t e2 = scratch ? hipStreamSynchronize(st) : hipSuccess;
+    if (scratch) (void)hipFree(scratch);
+    if (e != hipSuccess) return fail(NMF_EHIP, "csc build: %s", hipGetErrorString(e));
+    if (e2 != hipSuccess) return fail(NMF_EHIP, "csc build: %s", hipGetErrorString(e2));
+    return NMF_OK;
+}
 
 }  // namespace
 
@@ -263,13 +294,12 @@ const char *nmf_last_error(void) { return t_err; }
 size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz, int32_t k,
                               int64_t batch_rows)
 {
-    (void)nnz;
     if (m < 1 || n < 1 || k < 1 || k > NMF_MU_MAX_K) return 0;
     switch (kind) {
     case 0:
     case 3: return dense_bytes(m, n, k, true);
     case 4: return dense_bytes(m, n, k, false);
-    case 1: return csr_bytes(n, k);
+    case 1: return nnz < 0 ? 0 : csr_bytes(n, nnz, k);
     case 2:
         if (batch_rows < 1) return 0;
         return dense_bytes(batch_rows < m ? batch_rows : m, n, k, false);
@@ -488,27 +518,44 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
     if (iters == 0) return NMF_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g.mu);
+    if (nnz >= ((int64_t)1 << 31) || m >= ((int64_t)1 << 31))
+        return fail(NMF_EUNSUPPORTED, "CSR path needs nnz < 2^31 and m < 2^31%s");
     void *ws = nullptr;
-    if (int rc = ensure_workspace(csr_bytes(n, k), &ws)) return rc;
+    if (int rc = ensure_workspace(csr_bytes(n, nnz, k), &ws)) return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
     float *Ht = cv.take<float>((size_t)n * k);
-    float *Pt = cv.take<float>((size_t)n * k);
+    int64_t *colptr = cv.take<int64_t>((size_t)n + 1);
+    int32_t *rowidx = cv.take<int32_t>((size_t)nnz);
+    float *cvals = cv.take<float>((size_t)nnz);
+
+    if (int rc = build_csc(rowptr, colidx, vals, m, n, nnz, colptr, rowidx, cvals, st)) return rc;
 
     NMF_HIP(launch_transpose(H, k, n, Ht, st));
     for (int it = 0; it < iters; ++it) {
         NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
-        NMF_HIP(launch_fill_zero(Pt, n * k, st));
-        NMF_HIP(launch_wta_csr(rowptr, colidx, vals, m, k, W, Pt, st));
-        NMF_HIP(launch_row_update(Ht, Pt, c.gw, n, k, eps, st));
+        NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, n, k, W, c.gw, Ht, eps, st));      // H update on H^T
         NMF_HIP(launch_gram_w(Ht, n, k, c.gh, c.gpart, c.counters, st));
-        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, m, k, Ht, c.gh, W, eps, st));
+        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, m, k, Ht, c.gh, W, eps, st));        // W update
     }
     NMF_HIP(launch_transpose(Ht, n, k, H, st));
     return NMF_OK;
 }
 
 // ---- single steps ----------------------------------------------------------
+
+int nmf_csr_to_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
+                   int64_t n, int64_t nnz, int64_t *colptr, int32_t *rowidx, float *cvals,
+                   void *stream)
+{
+    if (!rowptr || !colptr) return fail(NMF_EINVAL, "null pointer%s");
+    if (m < 1 || n < 1 || nnz < 0) return fail(NMF_EINVAL, "bad size%s");
+    if (nnz > 0 && (!colidx || !vals || !rowidx || !cvals)) return fail(NMF_EINVAL, "null pointer%s");
+    if (nnz >= ((int64_t)1 << 31) || m >= ((int64_t)1 << 31))
+        return fail(NMF_EUNSUPPORTED, "CSR path needs nnz < 2^31 and m < 2^31%s");
+    return build_csc(rowptr, colidx, vals, m, n, nnz, colptr, rowidx, cvals,
+                     static_cast<hipStream_t>(stream));
+}
 
 int nmf_gram_w(const float *W, int64_t m, int32_t k, float *G, void *stream)
 {

@@ -1,19 +1,27 @@
 // CSR kernels of the multiplicative-update iteration for gfx950 (MI355X).
 //
 // With A in CSR (paper, section 2.3: values, column indices, row pointers) the
-// two products over A become sums over stored entries:
-//   A H^T : Q[i][:]  = sum over entries (i, j, a) of a * Ht[j][:]     (gather)
-//   W^T A : Pt[j][:] += a * W[i][:] for every entry (i, j, a)         (scatter)
-// Both are written against a transposed factor Ht = H^T (n x k), so that one
-// stored entry touches one contiguous run of k floats.  The whole sparse
-// iteration therefore works on Ht; H itself is transposed once on entry and
-// once on exit.
+// two products over A become sums over stored entries.  Both are run as
+// gathers against a row-major factor table, so that one stored entry touches
+// one contiguous run of k floats and no atomics are needed:
+//   A H^T : Q[i][:]  = sum over the entries (i, j, a) of row i    of a * Ht[j][:]
+//   W^T A : Pt[j][:] = sum over the entries (i, j, a) of column j of a * W[i][:]
+// The first walks the caller's CSR arrays (read-only, never copied); the
+// second walks a column-ordered copy (CSC: column pointers, row indices,
+// values) that is built once per call by a stable radix sort of the column
+// indices, so entries of a column keep their row order and sums are
+// reproducible.  The two updates are then one kernel used twice (the H update
+// is the W update of the transposed problem), each with its update fused.
+// The sparse iteration works on Ht = H^T (n x k); H is transposed on entry
+// and on exit.
 //
-// Work mapping: a row (or a column of H) is handled by a group of LPR lanes,
-// LPR = smallest power of two >= k (at least 4): lane c of the group owns
-// factor index c.  A wave holds 64 / LPR rows, so short rows are packed
-// several to a wave.  The group reads its row's entries LPR at a time with
-// coalesced loads and hands them round with lane shuffles.
+// Work mapping: a row (of A for the W update, of A^T for the H update) is
+// handled by a group of LPR lanes, LPR = smallest power of two >= k (at least
+// 4): lane c of the group owns factor index c.  A wave holds 64 / LPR rows, so
+// short rows are packed several to a wave.  The group reads its row's entries
+// LPR at a time with coalesced loads and hands them round with lane shuffles.
+#include <hipcub/hipcub.hpp>
+
 #include "nmfmu_internal.h"
 
 namespace nmfmu {
@@ -83,10 +91,22 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
                 colv = colidx[e + c];
                 valv = vals[e + c];
             }
-            for (int t = 0; __any(t < cnt); ++t) {
-                const int col = group_bcast<LPR>(colv, t);
-                const float a = group_bcast<LPR>(valv, t);
-                if (t < cnt && c < k) acc += a * Ht[(int64_t)col * k + c];
+            // Entries are taken UNR at a time: all their gathers are issued before
+            // the first multiply, so several cache lines per group are in flight.
+            // Lanes past the end of the row hold (column 0, value 0): they gather
+            // row 0 of the table and add nothing.
+            constexpr int UNR = (LPR < 8) ? LPR : 8;
+            const int cc = (c < k) ? c : 0;
+            for (int t0 = 0; __any(t0 < cnt); t0 += UNR) {
+                float a[UNR], h[UNR];
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) {
+                    const int col = group_bcast<LPR>(colv, t0 + u);
+                    a[u] = group_bcast<LPR>(valv, t0 + u);
+                    h[u] = Ht[(int64_t)col * k + cc];
+                }
+#pragma unroll
+                for (int u = 0; u < UNR; ++u) acc += a[u] * h[u];
             }
             e += LPR;
         }
@@ -97,69 +117,51 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
 }
 
 // ---------------------------------------------------------------------------
-// Pt (n x k) += scatter of a * W[i][:] over the stored entries.  Algorithm 3,
-// formation of WTA, for a CSR A; fp32 hardware atomics, order not fixed.
+// Column-ordered copy of the CSR matrix.
 // ---------------------------------------------------------------------------
-template <int LPR>
-__global__ __launch_bounds__(256) void wta_csr_kernel(const int64_t *__restrict__ rowptr,
-                                                      const int32_t *__restrict__ colidx,
-                                                      const float *__restrict__ vals, int64_t m,
-                                                      int k, const float *__restrict__ W, float *Pt)
+// payload[e] = (row of entry e) << 32 | bits of vals[e]; a group of 32 lanes per row.
+__global__ __launch_bounds__(256) void csc_payload_kernel(const int64_t *__restrict__ rowptr,
+                                                          const float *__restrict__ vals, int64_t m,
+                                                          uint64_t *__restrict__ payload)
 {
-    const int c = threadIdx.x % LPR;
-    const int64_t group = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
-    const int64_t ngroups = (int64_t)gridDim.x * 256 / LPR;
-    const int64_t trips = (m + ngroups - 1) / ngroups;
-    for (int64_t it = 0; it < trips; ++it) {
-        const int64_t row = group + it * ngroups;
-        const bool valid = row < m;
-        int64_t e = valid ? rowptr[row] : 0;
-        const int64_t e1 = valid ? rowptr[row + 1] : 0;
-        const float w = (valid && c < k) ? W[row * k + c] : 0.f;
-        while (__any(e < e1)) {
-            const int64_t left = e1 - e;
-            const int cnt = left < LPR ? (left > 0 ? (int)left : 0) : LPR;
-            int colv = 0;
-            float valv = 0.f;
-            if (c < cnt) {
-                colv = colidx[e + c];
-                valv = vals[e + c];
-            }
-            for (int t = 0; __any(t < cnt); ++t) {
-                const int col = group_bcast<LPR>(colv, t);
-                const float a = group_bcast<LPR>(valv, t);
-                if (t < cnt && c < k) unsafeAtomicAdd(&Pt[(int64_t)col * k + c], a * w);
-            }
-            e += LPR;
-        }
+    const int c = threadIdx.x & 31;
+    const int64_t group = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 5;
+    const int64_t ngroups = (int64_t)gridDim.x * 8;
+    for (int64_t row = group; row < m; row += ngroups) {
+        const int64_t e1 = rowptr[row + 1];
+        for (int64_t e = rowptr[row] + c; e < e1; e += 32)
+            payload[e] = ((uint64_t)row << 32) | (uint64_t)__float_as_uint(vals[e]);
     }
 }
 
-// ---------------------------------------------------------------------------
-// X <- X * Q / (X G + eps) row by row, X and Q rows x k, G symmetric k x k.
-// With X = Ht, Q = Pt, G = WTW this is the H update of Algorithm 3 written
-// for the transposed factor.
-// ---------------------------------------------------------------------------
-template <int LPR>
-__global__ __launch_bounds__(256) void row_update_kernel(float *X, const float *__restrict__ Q,
-                                                         const float *__restrict__ G, int64_t rows,
-                                                         int k, float eps)
+// After the stable sort by column: sorted_cols[e'] is the column of the e'-th
+// entry in column order and sorted_payload[e'] its (row, value).  Writes the CSC
+// row indices and values and the column pointers (every column j with
+// sorted_cols[e'-1] < j <= sorted_cols[e'] starts at e'; columns after the last
+// stored one start at nnz).
+__global__ __launch_bounds__(256) void csc_finish_kernel(const int32_t *__restrict__ sorted_cols,
+                                                         const uint64_t *__restrict__ sorted_payload,
+                                                         int64_t n, int64_t nnz,
+                                                         int64_t *__restrict__ colptr,
+                                                         int32_t *__restrict__ rowidx,
+                                                         float *__restrict__ cvals)
 {
-    constexpr int LDG = 65;
-    __shared__ float Gs[64 * LDG];
-    stage_gram(Gs, G, k, LDG);
-    const int c = threadIdx.x % LPR;
-    const int64_t group = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
-    const int64_t ngroups = (int64_t)gridDim.x * 256 / LPR;
-    const int64_t trips = (rows + ngroups - 1) / ngroups;
-    for (int64_t it = 0; it < trips; ++it) {
-        const int64_t row = group + it * ngroups;
-        const bool ok = row < rows && c < k;
-        const float x = ok ? X[row * k + c] : 0.f;
-        const float q = ok ? Q[row * k + c] : 0.f;
-        const float den = row_times_gram<LPR>(x, Gs, LDG, k, c) + eps;
-        if (ok) X[row * k + c] = x * q / den;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < nnz; e += (int64_t)gridDim.x * 256) {
+        const uint64_t pl = sorted_payload[e];
+        rowidx[e] = (int32_t)(pl >> 32);
+        cvals[e] = __uint_as_float((unsigned)pl);
+        const int64_t cur = sorted_cols[e];
+        const int64_t prev = (e > 0) ? sorted_cols[e - 1] : -1;
+        for (int64_t j = prev + 1; j <= cur; ++j) colptr[j] = e;
+        if (e == nnz - 1)
+            for (int64_t j = cur + 1; j <= n; ++j) colptr[j] = nnz;
     }
+}
+
+__global__ __launch_bounds__(256) void fill_i64_kernel(int64_t *p, int64_t count, int64_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+        p[i] = v;
 }
 
 // out (cols x rows) = in^T, in is rows x cols.
@@ -178,12 +180,6 @@ __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict_
             if (c0 + y < cols && r0 + tx < rows) out[(c0 + y) * rows + r0 + tx] = tile[tx][y];
         __syncthreads();
     }
-}
-
-__global__ __launch_bounds__(256) void fill_zero_kernel(float *p, int64_t count)
-{
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
-        p[i] = 0.f;
 }
 
 // ---------------------------------------------------------------------------
@@ -225,26 +221,6 @@ hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const fl
     return hipGetLastError();
 }
 
-hipError_t launch_wta_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
-                          int64_t m, int k, const float *W, float *Pt, hipStream_t st)
-{
-    const int lpr = lanes_per_row(k);
-    dim3 grid(blocks_for_groups(m, lpr));
-    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((wta_csr_kernel<L>), grid, dim3(256), 0, st, rowptr,
-                                             colidx, vals, m, k, W, Pt));
-    return hipGetLastError();
-}
-
-hipError_t launch_row_update(float *X, const float *Q, const float *G, int64_t rows, int k,
-                             float eps, hipStream_t st)
-{
-    const int lpr = lanes_per_row(k);
-    dim3 grid(blocks_for_groups(rows, lpr));
-    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((row_update_kernel<L>), grid, dim3(256), 0, st, X, Q,
-                                             G, rows, k, eps));
-    return hipGetLastError();
-}
-
 hipError_t launch_transpose(const float *in, int64_t rows, int64_t cols, float *out, hipStream_t st)
 {
     int64_t tiles = ((rows + 31) / 32) * ((cols + 31) / 32);
@@ -253,12 +229,49 @@ hipError_t launch_transpose(const float *in, int64_t rows, int64_t cols, float *
     return hipGetLastError();
 }
 
-hipError_t launch_fill_zero(float *p, int64_t count, hipStream_t st)
+static unsigned blocks_for(int64_t count)
 {
     int64_t b = (count + 255) / 256;
-    if (b > 8192) b = 8192;
+    if (b > 65536) b = 65536;
     if (b < 1) b = 1;
-    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)b), dim3(256), 0, st, p, count);
+    return (unsigned)b;
+}
+
+static int bits_for(int64_t n)
+{
+    int b = 1;
+    while (((int64_t)1 << b) < n) ++b;
+    return b;
+}
+
+size_t csc_sort_temp_bytes(int64_t nnz, int64_t n)
+{
+    size_t bytes = 0;
+    const int32_t *kin = nullptr;
+    int32_t *kout = nullptr;
+    const uint64_t *vin = nullptr;
+    uint64_t *vout = nullptr;
+    (void)hipcub::DeviceRadixSort::SortPairs(nullptr, bytes, kin, kout, vin, vout, (int)nnz, 0, bits_for(n));
+    return bytes;
+}
+
+hipError_t launch_csc_build(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                            int64_t m, int64_t n, int64_t nnz, int32_t *sorted_cols,
+                            uint64_t *payload, uint64_t *sorted_payload, void *sort_temp,
+                            size_t sort_temp_bytes, int64_t *colptr, int32_t *rowidx, float *cvals,
+                            hipStream_t st)
+{
+    if (nnz == 0) {
+        hipLaunchKernelGGL(fill_i64_kernel, dim3(blocks_for(n + 1)), dim3(256), 0, st, colptr, n + 1, (int64_t)0);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(csc_payload_kernel, dim3(blocks_for(m * 32)), dim3(256), 0, st, rowptr, vals, m, payload);
+    hipError_t e = hipcub::DeviceRadixSort::SortPairs(sort_temp, sort_temp_bytes, colidx, sorted_cols,
+                                                      (const uint64_t *)payload, sorted_payload,
+                                                      (int)nnz, 0, bits_for(n), st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(csc_finish_kernel, dim3(blocks_for(nnz)), dim3(256), 0, st, sorted_cols,
+                       sorted_payload, n, nnz, colptr, rowidx, cvals);
     return hipGetLastError();
 }
 

@@ -54,17 +54,23 @@ hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const
                            const float *GH, float *W, float eps, hipStream_t st);
 
 // ---- CSR (everything in terms of Ht = H^T, n x k) ----
+// X[i][:] <- X[i][:] * (sum over the stored entries (i, j, a) of a * T[j][:]) / (X[i][:] G + eps)
+// for i < rows.  W update: (rowptr, colidx, vals) = CSR of A, T = Ht, G = H H^T, X = W.
+// H update: the CSC arrays of A, T = W, G = W^T W, X = Ht.
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           int64_t m, int k, const float *Ht, const float *GH, float *W, float eps,
                           hipStream_t st);
-// Pt (n x k) += A^T W by scattering stored entries (fp32 atomics); zero Pt first.
-hipError_t launch_wta_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
-                          int64_t m, int k, const float *W, float *Pt, hipStream_t st);
-// X <- X * Q / (X G + eps) row by row (X, Q rows x k; G symmetric k x k).
-hipError_t launch_row_update(float *X, const float *Q, const float *G, int64_t rows, int k,
-                             float eps, hipStream_t st);
+// Column-ordered copy (colptr int64[n+1], rowidx int32[nnz], cvals float[nnz]) of a CSR matrix
+// by a stable sort on the column index.  Scratch: sorted_cols int32[nnz], payload and
+// sorted_payload uint64[nnz], sort_temp of csc_sort_temp_bytes(nnz, n) bytes.
+// nnz < 2^31, m < 2^31.
+size_t csc_sort_temp_bytes(int64_t nnz, int64_t n);
+hipError_t launch_csc_build(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                            int64_t m, int64_t n, int64_t nnz, int32_t *sorted_cols,
+                            uint64_t *payload, uint64_t *sorted_payload, void *sort_temp,
+                            size_t sort_temp_bytes, int64_t *colptr, int32_t *rowidx, float *cvals,
+                            hipStream_t st);
 // out (cols x rows) = in^T.
 hipError_t launch_transpose(const float *in, int64_t rows, int64_t cols, float *out, hipStream_t st);
-hipError_t launch_fill_zero(float *p, int64_t count, hipStream_t st);
 
 }  // namespace nmfmu

@@ -314,6 +314,49 @@ def test_csr_unsorted_duplicates_empty_rows_equal_dense():
     assert (Wg[10] == 0).all() and (Wg[m - 1] == 0).all()
 
 
+@pytest.mark.parametrize("m,n,density,scramble", [(300, 500, 0.02, False), (64, 48, 0.3, True),
+                                                  (5000, 3000, 0.004, True), (7, 2000, 0.01, False)])
+def test_csc_structure_is_bit_exact(m, n, density, scramble):
+    """The column-ordered copy (integer work): column pointers, row indices and
+    values must equal a stable host sort of the stored entries by column,
+    exactly, including unsorted rows, duplicates and empty columns."""
+    rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(m, n, density, seed=93))
+    if scramble:
+        r = np.random.default_rng(94)
+        colidx = colidx.copy(); vals = vals.copy()
+        for i in range(m):
+            a, b = rowptr[i], rowptr[i + 1]
+            p = r.permutation(b - a)
+            colidx[a:b] = colidx[a:b][p]
+            vals[a:b] = vals[a:b][p]
+            if b - a >= 2:
+                colidx[a] = colidx[a + 1]          # a repeated (row, column) pair
+    nnz = int(vals.size)
+    rows = np.repeat(np.arange(m, dtype=np.int32), np.diff(rowptr))
+    order = np.argsort(colidx, kind="stable")
+    want_rowidx, want_vals = rows[order], vals[order]
+    want_colptr = np.zeros(n + 1, dtype=np.int64)
+    want_colptr[1:] = np.cumsum(np.bincount(colidx, minlength=n))
+    colptr = torch.empty(n + 1, dtype=torch.int64, device="cuda")
+    rowidx = torch.empty(nnz, dtype=torch.int32, device="cuda")
+    cvals = torch.empty(nnz, dtype=torch.float32, device="cuda")
+    nmf.nmf_csr_to_csc(dev(rowptr, torch.int64), dev(colidx, torch.int32), dev(vals), m, n, nnz,
+                       colptr, rowidx, cvals)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(colptr.cpu().numpy(), want_colptr)
+    np.testing.assert_array_equal(rowidx.cpu().numpy(), want_rowidx)
+    np.testing.assert_array_equal(cvals.cpu().numpy(), want_vals)
+
+
+def test_csr_is_reproducible_run_to_run():
+    rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(3000, 2000, 0.01, seed=98))
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(3000, 2000, 32, seed=99))
+    W1, H1 = run_csr(rowptr, colidx, vals, 3000, 2000, W, H, 3)
+    W2, H2 = run_csr(rowptr, colidx, vals, 3000, 2000, W, H, 3)
+    np.testing.assert_array_equal(W1, W2)
+    np.testing.assert_array_equal(H1, H2)
+
+
 def test_csr_empty_matrix():
     m, n, k = 20, 30, 3
     rowptr = np.zeros(m + 1, dtype=np.int64)
