@@ -138,6 +138,10 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k,
  * (k[r] x n).  A[r] may be the same pointer for several runs; W[r], H[r] must
  * not overlap.  The pointer arrays and k live in HOST memory and are read
  * before the call returns; what they point to is device memory.
+ * Consecutive runs that name the same A are stacked while their ranks sum to at
+ * most NMF_MU_MAX_K: the two passes over A then serve the whole stack at once
+ * (order the runs by A to benefit).  Results per run equal a single run's up
+ * to rounding order.
  */
 int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64_t n,
                          const int32_t *k, float *const *W, float *const *H,
@@ -148,7 +152,8 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
  * library keeps a transposed copy of A, so this is about m*n*4 bytes plus the
  * partial sums), 4 dense (small plan: partial sums only; used automatically
  * when the fast plan's workspace cannot be had), 1 csr, 2 ooc (excluding the
- * staging slots), 3 batched with k = largest rank.  0 on invalid arguments.
+ * staging slots), 3 batched (enough for any mix of ranks; k is only checked).
+ * 0 on invalid arguments.
  */
 size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz,
                               int32_t k, int64_t batch_rows);

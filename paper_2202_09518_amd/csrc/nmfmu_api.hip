@@ -193,7 +193,7 @@ constexpr int kDenseKernels = 6;
 // to zero duration.  `a_is_mirrored`: At already holds this A's transpose.
 int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, int iters,
                float eps, const DensePlan &p, hipStream_t st, bool a_is_mirrored = false,
-               hipEvent_t *ev = nullptr)
+               hipEvent_t *ev = nullptr, const BlockMap *map = nullptr)
 {
     const Common &c = p.c;
     if (p.mirrored) {
@@ -213,12 +213,12 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, p.s1, p.rps1, false, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, p.s1, nullptr, c.gwp, nbw, c.ghp, k, n, eps, st));
+            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, p.s1, nullptr, c.gwp, nbw, c.ghp, k, n, eps, st, map));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.ppart, p.s2, p.rps2, false, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, p.s2, nullptr, c.ghp, nbh, c.gwp, k, m, eps, st));
+            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, p.s2, nullptr, c.ghp, nbh, c.gwp, k, m, eps, st, map));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         }
         return NMF_OK;
@@ -296,8 +296,10 @@ size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz, int32
 {
     if (m < 1 || n < 1 || k < 1 || k > NMF_MU_MAX_K) return 0;
     switch (kind) {
-    case 0:
-    case 3: return dense_bytes(m, n, k, true);
+    case 0: return dense_bytes(m, n, k, true);
+    case 3:   // stacks of runs up to the largest supported rank, plus their packed factors
+        return dense_bytes(m, n, NMF_MU_MAX_K, true) + align_up((size_t)m * NMF_MU_MAX_K * sizeof(float)) +
+               align_up((size_t)NMF_MU_MAX_K * n * sizeof(float));
     case 4: return dense_bytes(m, n, k, false);
     case 1: return nnz < 0 ? 0 : csr_bytes(n, nnz, k);
     case 2:
@@ -418,17 +420,81 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
     }
     if (iters == 0 || n_runs == 0) return NMF_OK;
     std::lock_guard<std::mutex> lock(g.mu);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // Consecutive runs on the same A are stacked side by side while their ranks sum to
+    // at most NMF_MU_MAX_K: one stack is one factorisation of rank sum(k) for the two
+    // passes over A (A is read once for all of them), with the Gram matrices masked to
+    // their diagonal blocks in the finishers so that the runs stay independent.
+    struct Stack { int first, count, K; };
+    std::vector<Stack> stacks;
+    for (int r = 0; r < n_runs;) {
+        Stack sk{r, 0, 0};
+        while (r < n_runs && A[r] == A[sk.first] && sk.K + k[r] <= NMF_MU_MAX_K) {
+            sk.K += k[r];
+            ++sk.count;
+            ++r;
+        }
+        stacks.push_back(sk);
+    }
+    int Kmax = kmax;
+    for (const Stack &sk : stacks)
+        if (sk.K > Kmax) Kmax = sk.K;
+    const size_t stack_bytes = align_up((size_t)m * Kmax * sizeof(float)) + align_up((size_t)Kmax * n * sizeof(float));
     void *ws = nullptr;
-    bool mirrored = false;
-    if (int rc = dense_workspace(m, n, kmax, &ws, &mirrored)) return rc;
-    // Carve once with the largest rank so that A^T sits at one address for all
-    // runs: consecutive runs on the same A then share its transpose.
-    const DensePlan p = carve_dense(ws, m, n, kmax, mirrored);
-    for (int r = 0; r < n_runs; ++r) {
-        const bool same_a = r > 0 && A[r] == A[r - 1];
-        if (int rc = dense_body(A[r], m, n, k[r], W[r], H[r], iters, eps, p,
-                                static_cast<hipStream_t>(stream), same_a))
+    // Stacking needs the mirrored plan for the largest stack plus room for the packed
+    // factors; without that much workspace the runs go one by one with the plan that fits.
+    const size_t big = dense_bytes(m, n, Kmax, true) + stack_bytes;
+    const bool can_stack = (g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK);
+    if (!can_stack) {
+        (void)hipGetLastError();
+        bool mirrored = false;
+        if (int rc = dense_workspace(m, n, kmax, &ws, &mirrored)) return rc;
+        const DensePlan p1 = carve_dense(ws, m, n, kmax, mirrored);
+        for (int r = 0; r < n_runs; ++r) {
+            const bool same_a = r > 0 && A[r] == A[r - 1];
+            if (int rc = dense_body(A[r], m, n, k[r], W[r], H[r], iters, eps, p1, st, same_a)) return rc;
+        }
+        return NMF_OK;
+    }
+    ws = g.ws;
+    // Carve once with the largest stacked rank so that A^T sits at one address for all
+    // stacks: consecutive stacks on the same A share its transpose.
+    const DensePlan p = carve_dense(ws, m, n, Kmax, true);
+    char *tail = static_cast<char *>(ws) + dense_bytes(m, n, Kmax, true);
+    float *Wall = reinterpret_cast<float *>(tail);
+    float *Hall = reinterpret_cast<float *>(tail + align_up((size_t)m * Kmax * sizeof(float)));
+    for (size_t si = 0; si < stacks.size(); ++si) {
+        const Stack &sk = stacks[si];
+        const bool same_a = si > 0 && A[sk.first] == A[stacks[si - 1].first];
+        if (sk.count == 1) {
+            const int r = sk.first;
+            if (int rc = dense_body(A[r], m, n, k[r], W[r], H[r], iters, eps, p, st, same_a)) return rc;
+            continue;
+        }
+        BlockMap map;
+        map.on = 1;
+        int off = 0;
+        for (int i = 0; i < sk.count; ++i) {
+            const int r = sk.first + i;
+            for (int c = 0; c < k[r]; ++c) map.id[off + c] = (unsigned char)i;
+            NMF_HIP(hipMemcpy2DAsync(Wall + off, (size_t)sk.K * sizeof(float), W[r], (size_t)k[r] * sizeof(float),
+                                     (size_t)k[r] * sizeof(float), (size_t)m, hipMemcpyDeviceToDevice, st));
+            NMF_HIP(hipMemcpyAsync(Hall + (size_t)off * n, H[r], (size_t)k[r] * n * sizeof(float),
+                                   hipMemcpyDeviceToDevice, st));
+            off += k[r];
+        }
+        for (int c = off; c < 64; ++c) map.id[c] = 255;
+        if (int rc = dense_body(A[sk.first], m, n, sk.K, Wall, Hall, iters, eps, p, st, same_a, nullptr, &map))
             return rc;
+        off = 0;
+        for (int i = 0; i < sk.count; ++i) {
+            const int r = sk.first + i;
+            NMF_HIP(hipMemcpy2DAsync(W[r], (size_t)k[r] * sizeof(float), Wall + off, (size_t)sk.K * sizeof(float),
+                                     (size_t)k[r] * sizeof(float), (size_t)m, hipMemcpyDeviceToDevice, st));
+            NMF_HIP(hipMemcpyAsync(H[r], Hall + (size_t)off * n, (size_t)k[r] * n * sizeof(float),
+                                   hipMemcpyDeviceToDevice, st));
+            off += k[r];
+        }
     }
     return NMF_OK;
 }

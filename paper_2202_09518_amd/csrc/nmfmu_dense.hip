@@ -296,7 +296,7 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                                                             const float *__restrict__ Gfull,
                                                             const float *__restrict__ gin, int nbin,
                                                             float *__restrict__ gout, int k,
-                                                            int64_t len, float eps)
+                                                            int64_t len, float eps, BlockMap bm)
 {
     constexpr int NW = 8, KT = KP / 32 > 0 ? KP / 32 : 1, NC = (KP + 7) / 8, LD = KP + 1;
     constexpr int LDT = 32 * KT + 1;   // the Gram tiles read 32 factor indices per tile
@@ -309,7 +309,8 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
     for (int e = tid; e < KP * KP; e += 64 * NW) {
         const int c = e / KP, d = e % KP;
         float v = 0.f;
-        if (c < k && d < k) {
+        // Stacked independent runs: factor indices of different runs do not interact.
+        if (c < k && d < k && (!bm.on || bm.id[c] == bm.id[d])) {
             if (Gfull) {
                 v = Gfull[c * k + d];
             } else {
@@ -353,12 +354,13 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
         float p[NC];
 #pragma unroll
         for (int ci = 0; ci < NC; ++ci) p[ci] = 0.f;
-        // Partial sums in split order; four splits' loads are issued together.
+        // Partial sums in split order; a few splits' loads are issued together.
+        constexpr int SB = (KP > 32) ? 2 : 4;
         int s = 0;
-        for (; s + 4 <= splits; s += 4) {
-            float t[4][NC];
+        for (; s + SB <= splits; s += SB) {
+            float t[SB][NC];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < SB; ++u)
 #pragma unroll
                 for (int ci = 0; ci < NC; ++ci) {
                     const int c = grp + 8 * ci;
@@ -367,7 +369,7 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                     t[u][ci] = in ? v : 0.f;
                 }
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < SB; ++u)
 #pragma unroll
                 for (int ci = 0; ci < NC; ++ci) p[ci] += t[u][ci];
         }
@@ -672,18 +674,21 @@ int factor_update_blocks(int64_t len)
 
 hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
                                 const float *Gfull, const float *gin, int nbin, float *gout, int k,
-                                int64_t len, float eps, hipStream_t st)
+                                int64_t len, float eps, hipStream_t st, const BlockMap *map)
 {
+    BlockMap bm;
+    if (map) bm = *map;
+    else bm.on = 0;
     // Without Gram output there is no reason to cap the grid: one block per chunk.
     int64_t blocks = gout ? factor_update_blocks(len) : (len + 63) / 64;
     if (blocks > 65535) blocks = 65535;
     const dim3 grid((unsigned)blocks), block(512);
     if (k <= 8)
-        hipLaunchKernelGGL((factor_update_kernel<8>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps);
+        hipLaunchKernelGGL((factor_update_kernel<8>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps, bm);
     else if (k <= 32)
-        hipLaunchKernelGGL((factor_update_kernel<32>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps);
+        hipLaunchKernelGGL((factor_update_kernel<32>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps, bm);
     else
-        hipLaunchKernelGGL((factor_update_kernel<64>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps);
+        hipLaunchKernelGGL((factor_update_kernel<64>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps, bm);
     return hipGetLastError();
 }
 

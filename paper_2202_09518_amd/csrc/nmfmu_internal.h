@@ -20,6 +20,13 @@ constexpr int kMaxKTiles = 2;       // 32-wide rank tiles: k <= 64
 
 inline int k_tiles(int k) { return (k + 31) / 32; }
 
+// Which independent run a factor index belongs to when several runs on the same A
+// are stacked side by side (id[c] for c < k); passed to kernels by value.
+struct BlockMap {
+    int on;
+    unsigned char id[64];
+};
+
 // Row split of the W^T A pass: number of partial k x n results, rows in each.
 int wta_splits(int64_t rows, int64_t n);
 int64_t wta_rows_per_split(int64_t rows, int splits);
@@ -44,7 +51,8 @@ hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, fl
 // of the new X, one set per block (factor_update_blocks(len) blocks).
 hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
                                 const float *Gfull, const float *gin, int nbin, float *gout, int k,
-                                int64_t len, float eps, hipStream_t st);
+                                int64_t len, float eps, hipStream_t st,
+                                const BlockMap *map = nullptr);
 int factor_update_blocks(int64_t len);
 // Blocks (= partial tile sets) launch_gram_w uses for `rows` rows; with G == nullptr it only
 // writes the partial tiles to gpart.

@@ -395,6 +395,35 @@ def test_batched_matches_loop_of_oracle_runs():
         check(host(Wd[r]), host(Hd[r]), Wr, Hr, 2e-4)
 
 
+def test_batched_stacks_runs_that_share_a():
+    """Copies outer, ranks inner: consecutive runs share A and are stacked
+    (34 = 2+3+8+16+5 in one stack, then 33 and 40 alone, per copy)."""
+    m, n = 384, 256
+    base = nmf_inputs.dense_planted(m, n, 8, seed=1005)
+    copies = [nmf_inputs.perturb(base, 3100 + p) for p in range(2)]
+    dA = [a.cuda() for a in copies]
+    ks_one = [2, 3, 8, 16, 5, 33, 40]
+    As, Ad, ks, Ws, Hs = [], [], [], [], []
+    for p in range(2):
+        for k in ks_one:
+            W, H = nmf_inputs.init_factors(m, n, k, seed=2105 + len(ks))
+            As.append(copies[p]); Ad.append(dA[p]); ks.append(k); Ws.append(W); Hs.append(H)
+    Wd = [w.cuda() for w in Ws]
+    Hd = [h.cuda() for h in Hs]
+    nmf.nmf_mu_dense_batched(len(ks), Ad, m, n, ks, Wd, Hd, 20, EPS)
+    worst = 0.0
+    for r in range(len(ks)):
+        Wr, Hr = orc.mu_dense(As[r].numpy(), Ws[r].numpy(), Hs[r].numpy(), 20, float(np.float32(EPS)))
+        worst = max(worst, check(host(Wd[r]), host(Hd[r]), Wr, Hr, 2e-4))
+    # one iteration, tight bar
+    Wd = [w.cuda() for w in Ws]
+    Hd = [h.cuda() for h in Hs]
+    nmf.nmf_mu_dense_batched(len(ks), Ad, m, n, ks, Wd, Hd, 1, EPS)
+    for r in range(len(ks)):
+        Wr, Hr = orc.mu_dense(As[r].numpy(), Ws[r].numpy(), Hs[r].numpy(), 1, float(np.float32(EPS)))
+        check(host(Wd[r]), host(Hd[r]), Wr, Hr, TOL1)
+
+
 # ---- workspace handling -----------------------------------------------------------------
 
 def test_caller_workspace_and_release():
