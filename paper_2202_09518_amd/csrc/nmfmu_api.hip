@@ -138,7 +138,8 @@ struct DensePlan {
 
 size_t dense_bytes(int64_t m, int64_t n, int k, bool mirrored)
 {
-    const size_t p1 = (size_t)wta_splits(m, n) * k * n, p2 = (size_t)wta_splits(n, m) * k * m;
+    // split counts shrink with k, so the count for rank 1 bounds every stack of rank <= k
+    const size_t p1 = (size_t)wta_splits(m, n, 1) * k * n, p2 = (size_t)wta_splits(n, m, 1) * k * m;
     size_t b = common_bytes(k) + align_up(((mirrored && p2 > p1) ? p2 : p1) * sizeof(float));
     if (mirrored)
         b += align_up((size_t)m * n * sizeof(float)) + align_up((size_t)k * m * sizeof(float)) +
@@ -152,11 +153,11 @@ DensePlan carve_dense(void *ws, int64_t m, int64_t n, int k, bool mirrored)
     DensePlan p;
     p.mirrored = mirrored;
     p.c = carve_common(cv, k);
-    p.s1 = wta_splits(m, n);
+    p.s1 = wta_splits(m, n, k);
     p.rps1 = wta_rows_per_split(m, p.s1);
-    p.s2 = wta_splits(n, m);
+    p.s2 = wta_splits(n, m, k);
     p.rps2 = wta_rows_per_split(n, p.s2);
-    const size_t p1 = (size_t)p.s1 * k * n, p2 = (size_t)p.s2 * k * m;
+    const size_t p1 = (size_t)wta_splits(m, n, 1) * k * n, p2 = (size_t)wta_splits(n, m, 1) * k * m;
     p.ppart = cv.take<float>((mirrored && p2 > p1) ? p2 : p1);
     p.At = p.Wt = p.Ht = nullptr;
     if (mirrored) {
@@ -196,6 +197,10 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
                hipEvent_t *ev = nullptr, const BlockMap *map = nullptr)
 {
     const Common &c = p.c;
+    // The plan may have been carved for a larger rank (stacks of an ensemble): split
+    // counts follow the rank actually run; the partial buffer holds the largest case.
+    const int s1 = wta_splits(m, n, k), s2 = wta_splits(n, m, k);
+    const int64_t rps1 = wta_rows_per_split(m, s1), rps2 = wta_rows_per_split(n, s2);
     if (p.mirrored) {
         if (!a_is_mirrored) NMF_HIP(launch_transpose(A, m, n, p.At, st));
         NMF_HIP(launch_transpose(W, m, k, p.Wt, st));
@@ -211,14 +216,14 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         for (int it = 0; it < iters; ++it) {
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, p.s1, p.rps1, false, st));
+            NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, s1, rps1, false, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, p.s1, nullptr, c.gwp, nbw, c.ghp, k, n, eps, st, map));
+            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, s1, nullptr, c.gwp, nbw, c.ghp, k, n, eps, st, map));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.ppart, p.s2, p.rps2, false, st));
+            NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.ppart, s2, rps2, false, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, p.s2, nullptr, c.ghp, nbh, c.gwp, k, m, eps, st, map));
+            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, nullptr, c.ghp, nbh, c.gwp, k, m, eps, st, map));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         }
         return NMF_OK;
@@ -227,9 +232,9 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
     for (int it = 0; it < iters; ++it) {
         NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, p.s1, p.rps1, false, st));
+        NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, s1, rps1, false, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        NMF_HIP(launch_factor_update(H, nullptr, p.ppart, p.s1, c.gw, nullptr, 0, nullptr, k, n, eps, st));
+        NMF_HIP(launch_factor_update(H, nullptr, p.ppart, s1, c.gw, nullptr, 0, nullptr, k, n, eps, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
@@ -519,7 +524,7 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
     if (int rc = ensure_workspace(dense_bytes(batch_rows, n, k, false), &ws)) return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
-    const int splits = wta_splits(batch_rows, n);
+    const int splits = wta_splits(batch_rows, n, k);
     const int64_t rps = wta_rows_per_split(batch_rows, splits);
     float *ppart = cv.take<float>((size_t)splits * k * n);
 
@@ -645,7 +650,7 @@ int nmf_wta_dense(const float *A, int64_t m, int64_t n, int32_t k, const float *
     if (int rc = ensure_workspace(dense_bytes(m, n, k, false), &ws)) return rc;
     Carve cv(ws);
     carve_common(cv, k);
-    const int splits = wta_splits(m, n);
+    const int splits = wta_splits(m, n, k);
     float *ppart = cv.take<float>((size_t)splits * k * n);
     NMF_HIP(launch_wta_pass(A, m, n, k, W, ppart, splits, wta_rows_per_split(m, splits), false, st));
     NMF_HIP(launch_sum_partials(ppart, splits, (int64_t)k * n, P, st));

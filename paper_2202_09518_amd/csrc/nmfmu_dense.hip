@@ -591,11 +591,15 @@ static inline bool vec_ok(const void *p, int64_t ld)
     return (reinterpret_cast<uintptr_t>(p) & 15u) == 0 && (ld & 3) == 0;
 }
 
-int wta_splits(int64_t rows, int64_t n)
+int wta_splits(int64_t rows, int64_t n, int k)
 {
+    // Enough workgroups to fill the chip once at the kernel's occupancy (4 groups per
+    // compute unit for k <= 32, 2 above), but long row ranges per group: every split
+    // costs a k x n partial result written and read again.
     const int64_t slabs = (n + kWtaCols - 1) / kWtaCols;
-    int64_t s = (2048 + slabs - 1) / slabs;          // aim at >= 2048 workgroups
-    const int64_t max_by_rows = (rows + 127) / 128;  // at least 128 rows per split
+    const int64_t target = (k <= 32) ? 1024 : 512;
+    int64_t s = (target + slabs - 1) / slabs;
+    const int64_t max_by_rows = (rows + 255) / 256;   // at least 256 rows per split
     if (s > max_by_rows) s = max_by_rows;
     if (s > 32) s = 32;
     if (s < 1) s = 1;
@@ -641,7 +645,7 @@ template <int KT>
 static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *W,
                          float *ppart, int64_t rows, int64_t n, int k, int64_t rps, int acc)
 {
-    constexpr int U = (KT == 1) ? 3 : 2, OCC = (KT == 1) ? 4 : 2;
+    constexpr int U = (KT == 1) ? 3 : 5, OCC = (KT == 1) ? 4 : 2;
     const dim3 block(64 * kWtaWaves);
     if (vec)
         hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, true>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);

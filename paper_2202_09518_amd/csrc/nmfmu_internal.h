@@ -28,7 +28,7 @@ struct BlockMap {
 };
 
 // Row split of the W^T A pass: number of partial k x n results, rows in each.
-int wta_splits(int64_t rows, int64_t n);
+int wta_splits(int64_t rows, int64_t n, int k);
 int64_t wta_rows_per_split(int64_t rows, int splits);
 
 // ---- kernel launchers (all asynchronous on `st`; return hipGetLastError) ----
