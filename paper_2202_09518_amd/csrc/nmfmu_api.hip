@@ -215,15 +215,17 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
         const int nbw = factor_update_blocks(m), nbh = factor_update_blocks(n);
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         for (int it = 0; it < iters; ++it) {
+            NMF_HIP(launch_gram_sum(c.gwp, nbw, k, c.gw, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             NMF_HIP(launch_wta_pass(A, m, n, k, W, p.ppart, s1, rps1, false, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, s1, nullptr, c.gwp, nbw, c.ghp, k, n, eps, st, map));
+            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, s1, c.gw, nullptr, 0, c.ghp, k, n, eps, st, map));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_gram_sum(c.ghp, nbh, k, c.gh, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.ppart, s2, rps2, false, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, nullptr, c.ghp, nbh, c.gwp, k, m, eps, st, map));
+            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, c.gh, nullptr, 0, c.gwp, k, m, eps, st, map));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         }
         return NMF_OK;

@@ -570,6 +570,40 @@ __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__
     }
 }
 
+// G (k x k, ld k) = sum over nb sets of partial 32 x 32 tiles (accumulator layout).
+// Eight lanes share one entry: lane q adds sets q, q+8, ... in order, then the
+// eight sums are combined in a fixed tree, so the result does not depend on timing.
+__global__ __launch_bounds__(256) void gram_sum_kernel(const float *__restrict__ gpart, int nb, int k,
+                                                       float *__restrict__ G)
+{
+    const int kt = (k + 31) >> 5;
+    const int64_t stride = (int64_t)kt * kt * 1024;
+    const int gid = blockIdx.x * 256 + threadIdx.x;
+    const int entry = gid >> 3, q = gid & 7;
+    const bool ok = entry < kt * kt * 1024;
+    const float *src = gpart + (ok ? entry : 0);
+    float s = 0.f;
+    int b = q;
+    for (; b + 24 < nb; b += 32) {
+        const float t0 = src[(b + 0) * stride], t1 = src[(b + 8) * stride];
+        const float t2 = src[(b + 16) * stride], t3 = src[(b + 24) * stride];
+        s += t0;
+        s += t1;
+        s += t2;
+        s += t3;
+    }
+    for (; b < nb; b += 8) s += src[b * stride];
+    s += __shfl_xor(s, 1, 8);
+    s += __shfl_xor(s, 2, 8);
+    s += __shfl_xor(s, 4, 8);
+    if (ok && q == 0) {
+        const int tile = entry >> 10, e = entry & 1023;
+        const int v = e >> 6, l = e & 63;
+        const int r1 = 32 * (tile / kt) + acc_row(v, l >> 5), r2 = 32 * (tile % kt) + (l & 31);
+        if (r1 < k && r2 < k) G[r1 * k + r2] = s;
+    }
+}
+
 // P = sum over the row splits of the partial W^T A results (test entry point only).
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float *__restrict__ ppart,
                                                            int splits, int64_t count,
@@ -668,6 +702,14 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
 }
 
 int gram_w_blocks(int64_t rows) { return gram_blocks(rows, 512); }
+
+hipError_t launch_gram_sum(const float *gpart, int nb, int k, float *G, hipStream_t st)
+{
+    const int kt = k_tiles(k);
+    const int threads = kt * kt * 1024 * 8;
+    hipLaunchKernelGGL(gram_sum_kernel, dim3((threads + 255) / 256), dim3(256), 0, st, gpart, nb, k, G);
+    return hipGetLastError();
+}
 
 int factor_update_blocks(int64_t len)
 {

@@ -15,7 +15,7 @@ constexpr int kWtaCols = 128;       // columns of A per workgroup in that pass
 constexpr int kAhtWaves = 8;        // waves per workgroup in the A H^T pass
 constexpr int kAhtRowTiles = 2;     // 32-row tiles per workgroup in that pass
 constexpr int kGramMaxBlocks = 64;  // partial Gram matrices before the final sum
-constexpr int kFinMaxBlocks = 128;  // finisher blocks when they also emit Gram partials
+constexpr int kFinMaxBlocks = 256;  // finisher blocks when they also emit Gram partials
 constexpr int kMaxKTiles = 2;       // 32-wide rank tiles: k <= 64
 
 inline int k_tiles(int k) { return (k + 31) / 32; }
@@ -54,6 +54,8 @@ hipError_t launch_factor_update(float *X, float *Xt, const float *part, int spli
                                 int64_t len, float eps, hipStream_t st,
                                 const BlockMap *map = nullptr);
 int factor_update_blocks(int64_t len);
+// G (k x k, ld k) = sum of nb sets of partial tiles.
+hipError_t launch_gram_sum(const float *gpart, int nb, int k, float *G, hipStream_t st);
 // Blocks (= partial tile sets) launch_gram_w uses for `rows` rows; with G == nullptr it only
 // writes the partial tiles to gpart.
 int gram_w_blocks(int64_t rows);
