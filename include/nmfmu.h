@@ -93,6 +93,27 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k,
                          float *kernel_ms);
 
 /*
+ * Objective of the factorisation, ||A - W H||_F (section 2.1; Algorithm 1
+ * evaluates it after every iteration).  W H is formed 32 rows at a time and
+ * never stored (the row tiling of section 3.2).  All of A, W, H on the device;
+ * the result is written to HOST memory after `stream` has been synchronised.
+ */
+int nmf_residual_dense(const float *A, int64_t m, int64_t n, int32_t k,
+                       const float *W, const float *H, double *residual_host, void *stream);
+
+/*
+ * Algorithm 1 with its stopping rule read as: iterate until ||A - W H||_F <= tol
+ * or max_iters iterations have run.  The objective is evaluated before the first
+ * iteration and then after every `check_every` iterations (each evaluation is
+ * one more pass over A and a stream synchronisation).  On return
+ * *iters_done_host iterations have been applied to W, H and *residual_host is
+ * the objective of the returned factors.  Blocking.
+ */
+int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                     int32_t max_iters, float eps, double tol, int32_t check_every,
+                     int32_t *iters_done_host, double *residual_host, void *stream);
+
+/*
  * Resident sparse MU: the same iteration with A given in CSR (section 2.3
  * names the three CSR arrays: values, column indices, row pointers).
  *   rowptr  device, int64[m + 1], non-decreasing, rowptr[0] = 0, rowptr[m] = nnz

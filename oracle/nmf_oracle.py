@@ -236,6 +236,23 @@ def residual_dense(A, W, H) -> float:
     return float(_load().oracle_residual_dense(_p(A), m, n, W.shape[1], _p(W), _p(H)))
 
 
+def mu_dense_tol(A, W0, H0, max_iters, eps, tol, check_every=1):
+    """Algorithm 1's loop: iterate (H then W) until ||A - W H||_F <= tol or
+    max_iters iterations have run; the objective is looked at before the first
+    iteration and after every `check_every` iterations.  Returns (W, H,
+    iterations applied, final objective)."""
+    W = _f64(W0)
+    H = _f64(H0)
+    done = 0
+    res = residual_dense(A, W, H)
+    while done < max_iters and res > tol:
+        chunk = min(check_every, max_iters - done)
+        W, H = mu_dense(A, W, H, chunk, eps)
+        done += chunk
+        res = residual_dense(A, W, H)
+    return W, H, done, res
+
+
 def mu_ensemble(As, W0s, H0s, iters, eps):
     """Independent runs, one after another (NMFk-style ensemble)."""
     return [mu_dense(A, W0, H0, iters, eps) for A, W0, H0 in zip(As, W0s, H0s)]

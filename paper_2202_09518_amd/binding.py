@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -50,6 +50,8 @@ def lib() -> ctypes.CDLL:
     L.nmf_last_error.restype = ctypes.c_char_p
     L.nmf_mu_dense.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp]
     L.nmf_mu_dense_profile.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp, vp]
+    L.nmf_residual_dense.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
+    L.nmf_mu_dense_tol.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
     L.nmf_mu_csr.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp]
     L.nmf_mu_ooc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
     L.nmf_mu_dense_batched.argtypes = [i32, vp, i64, i64, vp, vp, vp, i32, f32, vp]
@@ -109,6 +111,24 @@ def nmf_mu_dense_profile(A, m, n, k, W, H, iters, eps, stream=None):
     _check(lib().nmf_mu_dense_profile(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
                                       _dev(H, torch.float32, "H"), iters, eps, _stream(stream), ms))
     return list(ms)
+
+
+def nmf_residual_dense(A, m, n, k, W, H, stream=None) -> float:
+    """||A - W H||_F (blocking)."""
+    out = ctypes.c_double()
+    _check(lib().nmf_residual_dense(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
+                                    _dev(H, torch.float32, "H"), ctypes.byref(out), _stream(stream)))
+    return out.value
+
+
+def nmf_mu_dense_tol(A, m, n, k, W, H, max_iters, eps, tol, check_every, stream=None):
+    """Returns (iterations applied, ||A - W H||_F of the returned factors); blocking."""
+    done = ctypes.c_int32()
+    res = ctypes.c_double()
+    _check(lib().nmf_mu_dense_tol(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
+                                  _dev(H, torch.float32, "H"), max_iters, eps, tol, check_every,
+                                  ctypes.byref(done), ctypes.byref(res), _stream(stream)))
+    return done.value, res.value
 
 
 def nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, stream=None) -> None:

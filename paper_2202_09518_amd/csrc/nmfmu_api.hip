@@ -615,6 +615,76 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
     return NMF_OK;
 }
 
+// ---- objective and tolerance-driven run ---------------------------------------
+
+namespace {
+// ||A - W H||_F into *out_host; synchronises `st`.  Scratch sits behind the dense plan.
+int residual_to_host(const float *A, int64_t m, int64_t n, int k, const float *W, const float *H,
+                     double *scratch, double *out_host, hipStream_t st)
+{
+    const int64_t blocks = (m + 31) / 32;
+    NMF_HIP(launch_residual(A, m, n, k, W, H, scratch + 1, scratch, st));
+    NMF_HIP(hipMemcpyAsync(out_host, scratch, sizeof(double), hipMemcpyDeviceToHost, st));
+    NMF_HIP(hipStreamSynchronize(st));
+    (void)blocks;
+    return NMF_OK;
+}
+size_t residual_scratch_bytes(int64_t m) { return align_up(((size_t)(m + 31) / 32 + 1) * sizeof(double)); }
+}  // namespace
+
+int nmf_residual_dense(const float *A, int64_t m, int64_t n, int32_t k, const float *W,
+                       const float *H, double *residual_host, void *stream)
+{
+    if (int rc = check_common(A, W, H, m, n, k, 0, 0.f)) return rc;
+    if (!residual_host) return fail(NMF_EINVAL, "null pointer%s");
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(kAlign + residual_scratch_bytes(m), &ws)) return rc;
+    Carve cv(ws);
+    cv.take<unsigned>(64);   // the arrival counters at the head of the workspace stay untouched
+    double *scratch = cv.take<double>((size_t)(m + 31) / 32 + 1);
+    return residual_to_host(A, m, n, k, W, H, scratch, residual_host, static_cast<hipStream_t>(stream));
+}
+
+int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                     int32_t max_iters, float eps, double tol, int32_t check_every,
+                     int32_t *iters_done_host, double *residual_host, void *stream)
+{
+    if (int rc = check_common(A, W, H, m, n, k, max_iters, eps)) return rc;
+    if (!iters_done_host || !residual_host) return fail(NMF_EINVAL, "null pointer%s");
+    if (!(tol >= 0.0) || check_every < 1) return fail(NMF_EINVAL, "tol must be >= 0 and check_every >= 1%s");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g.mu);
+    void *ws = nullptr;
+    bool mirrored = false;
+    // the residual scratch rides behind whichever dense plan fits
+    const size_t extra = residual_scratch_bytes(m);
+    const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
+    if ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK)) {
+        mirrored = true;
+    } else {
+        (void)hipGetLastError();
+        if (int rc = ensure_workspace(small, &ws)) return rc;
+    }
+    ws = g.ws;
+    const DensePlan p = carve_dense(ws, m, n, k, mirrored);
+    double *scratch = reinterpret_cast<double *>(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
+    int done = 0;
+    double res = 0.0;
+    if (int rc = residual_to_host(A, m, n, k, W, H, scratch, &res, st)) return rc;
+    bool have_at = false;
+    while (done < max_iters && res > tol) {
+        const int chunk = (max_iters - done < check_every) ? max_iters - done : check_every;
+        if (int rc = dense_body(A, m, n, k, W, H, chunk, eps, p, st, have_at)) return rc;
+        have_at = mirrored;
+        done += chunk;
+        if (int rc = residual_to_host(A, m, n, k, W, H, scratch, &res, st)) return rc;
+    }
+    *iters_done_host = done;
+    *residual_host = res;
+    return NMF_OK;
+}
+
 // ---- single steps ----------------------------------------------------------
 
 int nmf_csr_to_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,

@@ -604,6 +604,79 @@ __global__ __launch_bounds__(256) void gram_sum_kernel(const float *__restrict__
     }
 }
 
+// ---------------------------------------------------------------------------
+// Objective ||A - W H||_F^2 in row tiles of W (the tiling of the paper's
+// section 3.2 for its convergence check: W H is produced tile by tile and never
+// stored).  Workgroup = 32 rows of A and W, 4 waves; a wave takes 128-column
+// slabs w, w+4, ...  Per slab: X = W_tile H[:, slab] by MFMA (A_op = W tile
+// from LDS, B_op = H elements, reduction over two factor indices per
+// instruction; column tile q holds columns j0 + 4 jj + q), then A is loaded in
+// the accumulator layout (16-byte loads, 512 contiguous bytes per row) and
+// (a - x)^2 is summed.  One double per workgroup goes to `partial`.
+// ---------------------------------------------------------------------------
+template <int KT, bool VEC>
+__global__ __launch_bounds__(256) void residual_kernel(const float *__restrict__ A,
+                                                       const float *__restrict__ W,
+                                                       const float *__restrict__ H, int64_t m,
+                                                       int64_t n, int k, double *__restrict__ partial)
+{
+    constexpr int KP = 32 * KT, LDW = KP + 1;
+    __shared__ float Ws[32 * LDW];
+    __shared__ double wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int jj = lane & 31, half = lane >> 5;
+    const int64_t i0 = (int64_t)blockIdx.x * 32;
+    for (int e = tid; e < 32 * KP; e += 256) {
+        const int i = e / KP, c = e % KP;
+        Ws[i * LDW + c] = (i0 + i < m && c < k) ? W[(i0 + i) * k + c] : 0.f;
+    }
+    __syncthreads();
+    const int kpairs = (k + 1) >> 1;
+    float local = 0.f;
+    double total = 0.0;
+    const int64_t nslabs = (n + 127) >> 7;
+    for (int64_t sl = w; sl < nslabs; sl += 4) {
+        const int64_t col = sl * 128 + 4 * jj;
+        f32x16 acc[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) acc[q] = f32x16{0};
+        for (int s = 0; s < kpairs; ++s) {
+            const int c = 2 * s + half;
+            const float a = Ws[jj * LDW + c];                 // c <= KP - 1 always; zero beyond k
+            const f32x4 h = load4<VEC>(H, n, c, col, c < k);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) acc[q] = mfma32(a, h[q], acc[q]);
+        }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int64_t row = i0 + acc_row(v, half);
+            const f32x4 a = load4<VEC>(A, n, row, col, row < m);
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const bool in = row < m && col + q < n;
+                const float d = in ? a[q] - acc[q][v] : 0.f;
+                local += d * d;
+            }
+        }
+        total += (double)local;     // fp32 within a slab (2048 terms per lane), double across slabs
+        local = 0.f;
+    }
+    for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off);
+    if (lane == 0) wsum[w] = total;
+    __syncthreads();
+    if (tid == 0) partial[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+// out[0] = sqrt(sum of `count` partials), added in index order by one thread.
+__global__ void residual_finish_kernel(const double *__restrict__ partial, int64_t count, double *out)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        double s = 0.0;
+        for (int64_t i = 0; i < count; ++i) s += partial[i];
+        out[0] = sqrt(s);
+    }
+}
+
 // P = sum over the row splits of the partial W^T A results (test entry point only).
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float *__restrict__ ppart,
                                                            int splits, int64_t count,
@@ -744,6 +817,23 @@ hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, fl
     int64_t b = (count + 255) / 256;
     if (b > 4096) b = 4096;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b), dim3(256), 0, st, ppart, splits, count, P);
+    return hipGetLastError();
+}
+
+hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const float *W,
+                           const float *H, double *partial, double *out, hipStream_t st)
+{
+    const int64_t blocks = (m + 31) / 32;
+    const bool vec = vec_ok(A, n) && vec_ok(H, n);
+    const dim3 grid((unsigned)blocks), block(256);
+    if (k_tiles(k) == 1) {
+        if (vec) hipLaunchKernelGGL((residual_kernel<1, true>), grid, block, 0, st, A, W, H, m, n, k, partial);
+        else hipLaunchKernelGGL((residual_kernel<1, false>), grid, block, 0, st, A, W, H, m, n, k, partial);
+    } else {
+        if (vec) hipLaunchKernelGGL((residual_kernel<2, true>), grid, block, 0, st, A, W, H, m, n, k, partial);
+        else hipLaunchKernelGGL((residual_kernel<2, false>), grid, block, 0, st, A, W, H, m, n, k, partial);
+    }
+    hipLaunchKernelGGL(residual_finish_kernel, dim3(1), dim3(64), 0, st, (const double *)partial, blocks, out);
     return hipGetLastError();
 }
 

@@ -63,6 +63,10 @@ int gram_w_blocks(int64_t rows);
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
                            const float *GH, float *W, float eps, hipStream_t st);
 
+// out[0] = ||A - W H||_F; partial: ceil(m / 32) doubles of scratch.
+hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const float *W,
+                           const float *H, double *partial, double *out, hipStream_t st);
+
 // ---- CSR (everything in terms of Ht = H^T, n x k) ----
 // X[i][:] <- X[i][:] * (sum over the stored entries (i, j, a) of a * T[j][:]) / (X[i][:] G + eps)
 // for i < rows.  W update: (rowptr, colidx, vals) = CSR of A, T = Ht, G = H H^T, X = W.

@@ -185,6 +185,55 @@ def test_dense_on_a_side_stream_and_unaligned_views():
     check(host(Wd), host(Hd), Wr, Hr, 2e-5)
 
 
+# ---- objective and tolerance-driven run --------------------------------------------
+
+@pytest.mark.parametrize("m,n,k", SHAPES + [(4096, 2048, 32)])
+def test_residual_dense(m, n, k):
+    A, W, H = case(m, n, k, 32)
+    got = nmf.nmf_residual_dense(dev(A), m, n, k, dev(W), dev(H))
+    want = orc.residual_dense(A, W, H)
+    assert abs(got - want) <= 1e-5 * want
+
+
+def test_residual_dense_small_residual():
+    """Near a good fit the objective is a small difference of large numbers:
+    the fp32 tiles must still give it to 1e-4."""
+    A, W, H = config1()
+    Wr, Hr = orc.mu_dense(A, W, H, 100, float(np.float32(EPS)))
+    Wf, Hf = Wr.astype(np.float32), Hr.astype(np.float32)
+    got = nmf.nmf_residual_dense(dev(A), 256, 192, 4, dev(Wf), dev(Hf))
+    want = orc.residual_dense(A, Wf, Hf)
+    assert want < 0.1 * np.linalg.norm(A)
+    assert abs(got - want) <= 1e-4 * want
+
+
+def test_mu_dense_tol_matches_algorithm_1_loop():
+    A, W, H = config1()
+    eps = float(np.float32(EPS))
+    traj = [orc.residual_dense(A, W, H)]
+    Wt, Ht = W, H
+    for _ in range(12):
+        Wt, Ht = orc.mu_dense(A, Wt, Ht, 5, eps)
+        traj.append(orc.residual_dense(A, Wt, Ht))
+    tol = 0.5 * (traj[7] + traj[8])
+    Wr, Hr, done_r, res_r = orc.mu_dense_tol(A, W, H, 1000, eps, tol, check_every=5)
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_dense_tol(dev(A), 256, 192, 4, Wd, Hd, 1000, EPS, tol, 5)
+    assert done == done_r == 40
+    assert abs(res - res_r) <= 1e-4 * res_r and res <= tol
+    check(host(Wd), host(Hd), Wr, Hr, TOLN)
+    # cap reached / tolerance already met
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_dense_tol(dev(A), 256, 192, 4, Wd, Hd, 7, EPS, 0.0, 5)
+    assert done == 7
+    W7, H7 = orc.mu_dense(A, W, H, 7, eps)
+    check(host(Wd), host(Hd), W7, H7, 1e-4)
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_dense_tol(dev(A), 256, 192, 4, Wd, Hd, 7, EPS, 1e9, 5)
+    assert done == 0 and abs(res - traj[0]) <= 1e-5 * traj[0]
+    np.testing.assert_array_equal(host(Wd), W.astype(np.float64))
+
+
 # ---- out-of-memory path -------------------------------------------------------
 
 @pytest.mark.parametrize("m,n,k,batch,slots,iters", [

@@ -467,3 +467,26 @@ def test_scipy_variant_equals_loop_oracle():
     W2, H2 = orc.mu_csr_scipy(rowptr, colidx, vals, m, n, W, H, 5, EPS)
     np.testing.assert_allclose(W2, W1, rtol=1e-11, atol=1e-300)
     np.testing.assert_allclose(H2, H1, rtol=1e-11, atol=1e-300)
+
+
+# --- Algorithm 1's loop with its stopping rule ------------------------------------------------
+
+def test_tolerance_loop_stops_where_the_objective_says():
+    A, W, H = config1()
+    traj = [orc.residual_dense(A, W, H)]
+    Wt, Ht = W, H
+    for _ in range(12):
+        Wt, Ht = orc.mu_dense(A, Wt, Ht, 5, EPS)
+        traj.append(orc.residual_dense(A, Wt, Ht))
+    tol = 0.5 * (traj[7] + traj[8])                   # first met after 8 checks = 40 iterations
+    Wo, Ho, done, res = orc.mu_dense_tol(A, W, H, 1000, EPS, tol, check_every=5)
+    assert done == 40 and res == traj[8] and res <= tol < traj[7]
+    W40, H40 = orc.mu_dense(A, W, H, 40, EPS)
+    np.testing.assert_array_equal(Wo, W40)
+    np.testing.assert_array_equal(Ho, H40)
+    # the iteration cap wins when the tolerance is out of reach; tol already met => no iteration
+    _, _, done, _ = orc.mu_dense_tol(A, W, H, 7, EPS, 0.0, check_every=5)
+    assert done == 7
+    Wn, Hn, done, res = orc.mu_dense_tol(A, W, H, 7, EPS, 1e9, check_every=5)
+    assert done == 0 and res == traj[0]
+    np.testing.assert_array_equal(Wn, W)
