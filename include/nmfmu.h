@@ -191,6 +191,14 @@ int nmf_mu_release(void);
 
 /* ---- single steps, exposed for testing and profiling (same conventions) ---- */
 
+/* The row-balanced work partition of the sparse kernels: part[0 .. nparts]
+ * (device, int64) with part[w] = first row r such that
+ * rowptr[r] + 8 r >= w * ceil((rowptr[m] + 8 m) / nparts) and part[nparts] = m;
+ * wavefront w of a sparse update works on rows [part[w], part[w + 1]).  The
+ * library uses nparts = 16384 and sends rows with more than 16384 stored
+ * entries to a whole workgroup instead.  Asynchronous on `stream`. */
+int nmf_csr_partition(const int64_t *rowptr, int64_t m, int32_t nparts, int64_t *part, void *stream);
+
 /* Column-ordered copy of a CSR matrix, the structure nmf_mu_csr derives for its
  * W^T A product: colptr int64[n + 1], rowidx int32[nnz], cvals float[nnz] (all
  * device, caller-allocated).  Entries of a column keep the order in which the

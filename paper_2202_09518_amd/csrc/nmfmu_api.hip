@@ -251,7 +251,10 @@ size_t csr_bytes(int64_t n, int64_t nnz, int k)
 {
     return common_bytes(k) + align_up((size_t)n * k * sizeof(float)) +      // Ht
            align_up((size_t)(n + 1) * sizeof(int64_t)) +                      // column pointers
-           align_up((size_t)nnz * sizeof(int32_t)) + align_up((size_t)nnz * sizeof(float));
+           align_up((size_t)nnz * sizeof(int32_t)) + align_up((size_t)nnz * sizeof(float)) +
+           2 * align_up((size_t)(kCsrParts + 1) * sizeof(int64_t)) +          // row ranges, CSR and CSC
+           2 * align_up((size_t)(nnz / kLongRow + 2) * sizeof(int32_t)) +     // long-row lists
+           kAlign;                                                            // their counts
 }
 
 // Column-ordered copy of a CSR matrix; the sort scratch is transient (allocated
@@ -601,15 +604,26 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
     int64_t *colptr = cv.take<int64_t>((size_t)n + 1);
     int32_t *rowidx = cv.take<int32_t>((size_t)nnz);
     float *cvals = cv.take<float>((size_t)nnz);
+    int64_t *part_r = cv.take<int64_t>((size_t)kCsrParts + 1);
+    int64_t *part_c = cv.take<int64_t>((size_t)kCsrParts + 1);
+    int32_t *long_r = cv.take<int32_t>((size_t)(nnz / kLongRow + 2));
+    int32_t *long_c = cv.take<int32_t>((size_t)(nnz / kLongRow + 2));
+    unsigned *long_n = cv.take<unsigned>(64);      // [0] rows of A, [1] columns of A
 
     if (int rc = build_csc(rowptr, colidx, vals, m, n, nnz, colptr, rowidx, cvals, st)) return rc;
+
+    // Work partitions of both orientations, once per call.
+    NMF_HIP(launch_csr_partition(rowptr, m, kCsrParts, part_r, st));
+    NMF_HIP(launch_csr_partition(colptr, n, kCsrParts, part_c, st));
+    NMF_HIP(launch_csr_long_rows(rowptr, m, long_r, long_n, st));
+    NMF_HIP(launch_csr_long_rows(colptr, n, long_c, long_n + 1, st));
 
     NMF_HIP(launch_transpose(H, k, n, Ht, st));
     for (int it = 0; it < iters; ++it) {
         NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
-        NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, n, k, W, c.gw, Ht, eps, st));      // H update on H^T
+        NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, W, c.gw, Ht, eps, st));   // H update on H^T
         NMF_HIP(launch_gram_w(Ht, n, k, c.gh, c.gpart, c.counters, st));
-        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, m, k, Ht, c.gh, W, eps, st));        // W update
+        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st));        // W update
     }
     NMF_HIP(launch_transpose(Ht, n, k, H, st));
     return NMF_OK;
@@ -686,6 +700,14 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
 }
 
 // ---- single steps ----------------------------------------------------------
+
+int nmf_csr_partition(const int64_t *rowptr, int64_t m, int32_t nparts, int64_t *part, void *stream)
+{
+    if (!rowptr || !part) return fail(NMF_EINVAL, "null pointer%s");
+    if (m < 1 || nparts < 1) return fail(NMF_EINVAL, "bad size%s");
+    NMF_HIP(launch_csr_partition(rowptr, m, nparts, part, static_cast<hipStream_t>(stream)));
+    return NMF_OK;
+}
 
 int nmf_csr_to_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
                    int64_t n, int64_t nnz, int64_t *colptr, int32_t *rowidx, float *cvals,

@@ -20,6 +20,9 @@
 // 4): lane c of the group owns factor index c.  A wave holds 64 / LPR rows, so
 // short rows are packed several to a wave.  The group reads its row's entries
 // LPR at a time with coalesced loads and hands them round with lane shuffles.
+// Rows are dealt to wavefronts in contiguous ranges of equal work (stored
+// entries plus a per-row cost), and rows too long for one group are split
+// over a whole workgroup.
 #include <hipcub/hipcub.hpp>
 
 #include "nmfmu_internal.h"
@@ -58,61 +61,161 @@ __device__ __forceinline__ void stage_gram(float *Gs, const float *__restrict__ 
 }
 
 // ---------------------------------------------------------------------------
-// W <- W * (A Ht) / (W GH + eps), A in CSR.  Algorithm 3: AHT, WHHT and the
-// W update in one kernel; the row of A H^T lives in one register per lane.
+// Row-balanced work partition.  The work of row r is taken as its stored
+// entries plus kRowCost (the fused update), so the running total
+//     key(r) = rowptr[r] + kRowCost * r
+// is increasing and part[w] = first r with key(r) >= w * share splits the rows
+// into nparts contiguous ranges of (nearly) equal work, one per wavefront.
+// Rows longer than kLongRow entries are taken out of the ranges (they would
+// stall one wavefront) and handled by a whole workgroup each.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void csr_partition_kernel(const int64_t *__restrict__ rowptr,
+                                                            int64_t m, int nparts,
+                                                            int64_t *__restrict__ part)
+{
+    const int w = blockIdx.x * 256 + threadIdx.x;
+    if (w > nparts) return;
+    const int64_t total = rowptr[m] + kRowCost * m;
+    const int64_t share = (total + nparts - 1) / nparts;
+    const int64_t target = (int64_t)w * share;
+    int64_t lo = 0, hi = m;                 // smallest r in [0, m] with key(r) >= target
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (rowptr[mid] + kRowCost * mid >= target) hi = mid;
+        else lo = mid + 1;
+    }
+    part[w] = (w == nparts) ? m : lo;
+}
+
+// list[0 .. *count) = rows with more than kLongRow entries (any order).
+__global__ __launch_bounds__(256) void csr_long_rows_kernel(const int64_t *__restrict__ rowptr,
+                                                            int64_t m, int32_t *__restrict__ list,
+                                                            unsigned *count)
+{
+    for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < m; r += (int64_t)gridDim.x * 256)
+        if (rowptr[r + 1] - rowptr[r] > kLongRow) list[atomicAdd(count, 1u)] = (int32_t)r;
+}
+
+__global__ void zero_u32_kernel(unsigned *p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0u; }
+
+// One gather step of a lane group: entries [e, e + LPR) of a row (fewer at its
+// end), UNR at a time so that several table rows are in flight; lanes past the
+// end hold (column 0, value 0): they gather row 0 of the table and add nothing.
+template <int LPR>
+__device__ __forceinline__ float gather_chunk(const int32_t *__restrict__ colidx,
+                                              const float *__restrict__ vals,
+                                              const float *__restrict__ T, int k, int c, int64_t e,
+                                              int64_t e1, float acc)
+{
+    const int64_t left = e1 - e;
+    const int cnt = left < LPR ? (left > 0 ? (int)left : 0) : LPR;
+    int colv = 0;
+    float valv = 0.f;
+    if (c < cnt) {
+        colv = colidx[e + c];
+        valv = vals[e + c];
+    }
+    constexpr int UNR = (LPR < 8) ? LPR : 8;
+    const int cc = (c < k) ? c : 0;
+    for (int t0 = 0; __any(t0 < cnt); t0 += UNR) {
+        float a[UNR], h[UNR];
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) {
+            const int col = group_bcast<LPR>(colv, t0 + u);
+            a[u] = group_bcast<LPR>(valv, t0 + u);
+            h[u] = T[(int64_t)col * k + cc];
+        }
+#pragma unroll
+        for (int u = 0; u < UNR; ++u) acc += a[u] * h[u];
+    }
+    return acc;
+}
+
+// ---------------------------------------------------------------------------
+// X[i][:] <- X[i][:] * (sum over the entries (i, j, a) of row i of a T[j][:]) / (X[i][:] G + eps).
+// With the CSR of A, T = Ht, G = H H^T, X = W: AHT, WHHT and the W update of
+// Algorithm 3 in one kernel (the row of A H^T lives in one register per lane);
+// with the column-ordered copy, T = W, G = W^T W, X = Ht: WTA and the H update.
+// Wavefront gw works on rows [part[gw], part[gw + 1]), 64 / LPR rows at a time.
 // ---------------------------------------------------------------------------
 template <int LPR>
 __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict__ rowptr,
                                                       const int32_t *__restrict__ colidx,
-                                                      const float *__restrict__ vals, int64_t m,
-                                                      int k, const float *__restrict__ Ht,
+                                                      const float *__restrict__ vals,
+                                                      const int64_t *__restrict__ part, int k,
+                                                      const float *__restrict__ Ht,
                                                       const float *__restrict__ GH, float *W,
                                                       float eps)
 {
-    constexpr int LDG = 65;
+    constexpr int LDG = 65, RPW = 64 / LPR;
     __shared__ float Gs[64 * LDG];
     stage_gram(Gs, GH, k, LDG);
-    const int c = threadIdx.x % LPR;
-    const int64_t group = ((int64_t)blockIdx.x * 256 + threadIdx.x) / LPR;
-    const int64_t ngroups = (int64_t)gridDim.x * 256 / LPR;
-    const int64_t trips = (m + ngroups - 1) / ngroups;     // same for every lane
-    for (int64_t it = 0; it < trips; ++it) {
-        const int64_t row = group + it * ngroups;
-        const bool valid = row < m;
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int64_t r_lo = part[gw], r_hi = part[gw + 1];          // same for the whole wavefront
+    for (int64_t base = r_lo; base < r_hi; base += RPW) {
+        const int64_t row = base + lane / LPR;
+        bool valid = row < r_hi;
         int64_t e = valid ? rowptr[row] : 0;
-        const int64_t e1 = valid ? rowptr[row + 1] : 0;
+        int64_t e1 = valid ? rowptr[row + 1] : 0;
+        if (e1 - e > kLongRow) {       // left to the long-row kernel
+            valid = false;
+            e1 = e;
+        }
         float acc = 0.f;
         while (__any(e < e1)) {
-            const int64_t left = e1 - e;
-            const int cnt = left < LPR ? (left > 0 ? (int)left : 0) : LPR;
-            int colv = 0;
-            float valv = 0.f;
-            if (c < cnt) {
-                colv = colidx[e + c];
-                valv = vals[e + c];
-            }
-            // Entries are taken UNR at a time: all their gathers are issued before
-            // the first multiply, so several cache lines per group are in flight.
-            // Lanes past the end of the row hold (column 0, value 0): they gather
-            // row 0 of the table and add nothing.
-            constexpr int UNR = (LPR < 8) ? LPR : 8;
-            const int cc = (c < k) ? c : 0;
-            for (int t0 = 0; __any(t0 < cnt); t0 += UNR) {
-                float a[UNR], h[UNR];
-#pragma unroll
-                for (int u = 0; u < UNR; ++u) {
-                    const int col = group_bcast<LPR>(colv, t0 + u);
-                    a[u] = group_bcast<LPR>(valv, t0 + u);
-                    h[u] = Ht[(int64_t)col * k + cc];
-                }
-#pragma unroll
-                for (int u = 0; u < UNR; ++u) acc += a[u] * h[u];
-            }
+            acc = gather_chunk<LPR>(colidx, vals, Ht, k, c, e, e1, acc);
             e += LPR;
         }
         const float w = (valid && c < k) ? W[row * k + c] : 0.f;
         const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
         if (valid && c < k) W[row * k + c] = w * acc / den;
+    }
+}
+
+// The same update for the rows in `list` (more than kLongRow entries): one
+// workgroup per row, its lane groups take the row's chunks round robin and
+// their sums are added in group order.
+template <int LPR>
+__global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__restrict__ rowptr,
+                                                           const int32_t *__restrict__ colidx,
+                                                           const float *__restrict__ vals,
+                                                           const int32_t *__restrict__ list,
+                                                           const unsigned *__restrict__ count, int k,
+                                                           const float *__restrict__ Ht,
+                                                           const float *__restrict__ GH, float *W,
+                                                           float eps)
+{
+    constexpr int LDG = 65, NG = 256 / LPR;
+    __shared__ float Gs[64 * LDG];
+    __shared__ float part_acc[NG][LPR];
+    const unsigned n_long = *count;
+    if (n_long == 0) return;
+    stage_gram(Gs, GH, k, LDG);
+    const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+    for (unsigned li = blockIdx.x; li < n_long; li += gridDim.x) {
+        const int64_t row = list[li];
+        const int64_t e0 = rowptr[row], e1 = rowptr[row + 1];
+        float acc = 0.f;
+        for (int64_t e = e0 + (int64_t)grp * LPR; __any(e < e1); e += (int64_t)NG * LPR)
+            acc = gather_chunk<LPR>(colidx, vals, Ht, k, c, e, e1, acc);
+        part_acc[grp][c] = acc;
+        __syncthreads();
+        if (grp == 0) {        // LPR is a multiple of 64 only for LPR = 64; smaller groups share a wave
+            float total = 0.f;
+            for (int gI = 0; gI < NG; ++gI) total += part_acc[gI][c];
+            part_acc[0][c] = total;
+        }
+        __syncthreads();
+        if (threadIdx.x < 64) {     // first wavefront: its first group finishes the row
+            const float tot = part_acc[0][c];
+            const bool mine = threadIdx.x < LPR;
+            const float w = (mine && c < k) ? W[row * k + c] : 0.f;
+            const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
+            if (mine && c < k) W[row * k + c] = w * tot / den;
+        }
+        __syncthreads();
     }
 }
 
@@ -191,16 +294,6 @@ static int lanes_per_row(int k)
     return l;
 }
 
-static unsigned blocks_for_groups(int64_t rows, int lpr)
-{
-    const int64_t groups_per_block = 256 / lpr;
-    int64_t b = (rows + groups_per_block - 1) / groups_per_block;
-    const int64_t cap = 256 * 16;       // 16 workgroups per compute unit, then grid-stride
-    if (b > cap) b = cap;
-    if (b < 1) b = 1;
-    return (unsigned)b;
-}
-
 #define NMFMU_LPR_SWITCH(lpr, CALL)      \
     switch (lpr) {                        \
     case 4: { constexpr int L = 4; CALL; } break;   \
@@ -210,14 +303,33 @@ static unsigned blocks_for_groups(int64_t rows, int lpr)
     default: { constexpr int L = 64; CALL; } break; \
     }
 
+hipError_t launch_csr_partition(const int64_t *rowptr, int64_t m, int nparts, int64_t *part,
+                                hipStream_t st)
+{
+    hipLaunchKernelGGL(csr_partition_kernel, dim3((nparts + 1 + 255) / 256), dim3(256), 0, st, rowptr, m, nparts, part);
+    return hipGetLastError();
+}
+
+hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list, unsigned *count,
+                                hipStream_t st)
+{
+    hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, count);
+    int64_t b = (m + 255) / 256;
+    if (b > 4096) b = 4096;
+    hipLaunchKernelGGL(csr_long_rows_kernel, dim3((unsigned)b), dim3(256), 0, st, rowptr, m, list, count);
+    return hipGetLastError();
+}
+
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
-                          int64_t m, int k, const float *Ht, const float *GH, float *W, float eps,
-                          hipStream_t st)
+                          const int64_t *part, const int32_t *long_list, const unsigned *long_count,
+                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st)
 {
     const int lpr = lanes_per_row(k);
-    dim3 grid(blocks_for_groups(m, lpr));
-    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_kernel<L>), grid, dim3(256), 0, st, rowptr,
-                                             colidx, vals, m, k, Ht, GH, W, eps));
+    const dim3 grid(kCsrParts / 4), block(256);
+    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_kernel<L>), grid, block, 0, st, rowptr, colidx,
+                                             vals, part, k, Ht, GH, W, eps));
+    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_long_kernel<L>), dim3(256), block, 0, st, rowptr,
+                                             colidx, vals, long_list, long_count, k, Ht, GH, W, eps));
     return hipGetLastError();
 }
 

@@ -71,9 +71,19 @@ hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const fl
 // X[i][:] <- X[i][:] * (sum over the stored entries (i, j, a) of a * T[j][:]) / (X[i][:] G + eps)
 // for i < rows.  W update: (rowptr, colidx, vals) = CSR of A, T = Ht, G = H H^T, X = W.
 // H update: the CSC arrays of A, T = W, G = W^T W, X = Ht.
+constexpr int kCsrParts = 16384;      // row ranges (= wavefronts) of a sparse update launch
+constexpr int64_t kRowCost = 8;       // work of a row besides its entries, in entries
+constexpr int64_t kLongRow = 16384;   // rows with more entries go to a whole workgroup
+// part[0 .. nparts]: row ranges of equal work; part[w] = first row r with
+// rowptr[r] + kRowCost * r >= w * ceil((rowptr[m] + kRowCost * m) / nparts), part[nparts] = m.
+hipError_t launch_csr_partition(const int64_t *rowptr, int64_t m, int nparts, int64_t *part,
+                                hipStream_t st);
+// list[0 .. *count): the rows with more than kLongRow entries (list needs nnz / kLongRow + 1 slots).
+hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list, unsigned *count,
+                                hipStream_t st);
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
-                          int64_t m, int k, const float *Ht, const float *GH, float *W, float eps,
-                          hipStream_t st);
+                          const int64_t *part, const int32_t *long_list, const unsigned *long_count,
+                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st);
 // Column-ordered copy (colptr int64[n+1], rowidx int32[nnz], cvals float[nnz]) of a CSR matrix
 // by a stable sort on the column index.  Scratch: sorted_cols int32[nnz], payload and
 // sorted_payload uint64[nnz], sort_temp of csc_sort_temp_bytes(nnz, n) bytes.

@@ -397,6 +397,64 @@ def test_csc_structure_is_bit_exact(m, n, density, scramble):
     np.testing.assert_array_equal(cvals.cpu().numpy(), want_vals)
 
 
+@pytest.mark.parametrize("m,nparts,kind", [(5000, 64, "uniform"), (5000, 16384, "uniform"), (300, 7, "skewed"),
+                                           (1, 4, "uniform"), (4000, 100, "empty")])
+def test_csr_partition_table_is_bit_exact(m, nparts, kind):
+    """Row ranges of equal work (integer work): the table must equal a host
+    bisection of key(r) = rowptr[r] + 8 r exactly."""
+    r = np.random.default_rng(m + nparts)
+    if kind == "uniform":
+        counts = r.poisson(20, m)
+    elif kind == "skewed":
+        counts = (r.pareto(1.0, m) * 5).astype(np.int64)
+        counts[17] = 50000
+    else:
+        counts = np.zeros(m, dtype=np.int64)
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(counts)
+    key = rowptr + 8 * np.arange(m + 1)
+    share = -(-int(key[m]) // nparts)
+    want = np.searchsorted(key, np.arange(nparts + 1) * share, side="left").astype(np.int64)
+    want = np.minimum(want, m)
+    want[nparts] = m
+    part = torch.empty(nparts + 1, dtype=torch.int64, device="cuda")
+    nmf.nmf_csr_partition(dev(rowptr, torch.int64), m, nparts, part)
+    torch.cuda.synchronize()
+    got = part.cpu().numpy()
+    np.testing.assert_array_equal(got, want)
+    assert got[0] == 0 and got[-1] == m and (np.diff(got) >= 0).all()
+
+
+def test_csr_skewed_rows_and_a_very_long_row():
+    """Power-law row lengths plus rows above the long-row threshold (handled by
+    a whole workgroup) and a long column, against the oracle."""
+    r = np.random.default_rng(77)
+    m, n, k = 400, 30000, 32
+    counts = np.minimum((r.pareto(1.2, m) * 8).astype(np.int64), n)
+    counts[5] = 20000            # long rows
+    counts[123] = 17000
+    counts[124] = 0
+    rows = []
+    for i in range(m):
+        rows.append(np.sort(r.choice(n, int(counts[i]), replace=False)).astype(np.int32))
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(counts)
+    colidx = np.concatenate(rows)
+    vals = (1.0 - r.random(colidx.size, dtype=np.float32)).astype(np.float32)
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=78))
+    Wg, Hg = run_csr(rowptr, colidx, vals, m, n, W, H, 2)
+    Wr, Hr = orc.mu_csr(rowptr, colidx, vals, m, n, W, H, 2, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 2 * TOL1)
+    # transposed problem: long columns of A become long rows of the column-ordered copy
+    import scipy.sparse as sp
+    At = sp.csr_matrix((vals, colidx, rowptr), shape=(m, n)).T.tocsr()
+    At.sort_indices()
+    Wt, Ht = (t.numpy() for t in nmf_inputs.init_factors(n, m, k, seed=79))
+    Wg, Hg = run_csr(At.indptr.astype(np.int64), At.indices.astype(np.int32), At.data.astype(np.float32), n, m, Wt, Ht, 2)
+    Wr, Hr = orc.mu_csr(At.indptr.astype(np.int64), At.indices.astype(np.int32), At.data.astype(np.float32), n, m, Wt, Ht, 2, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 2 * TOL1)
+
+
 def test_csr_is_reproducible_run_to_run():
     rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(3000, 2000, 0.01, seed=98))
     W, H = (t.numpy() for t in nmf_inputs.init_factors(3000, 2000, 32, seed=99))
