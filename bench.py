@@ -79,9 +79,14 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
     kern = dict(zip(names, kms[:6]))
     log("[bench] plan:", "mirrored (A and A^T resident)" if kms[6] else "direct")
     log("[bench] per-kernel ms:", {a: round(b, 4) for a, b in kern.items()})
-    dom = max(("wta_pass", "aht_pass"), key=lambda x: kern[x])
+    # the two pass kernels alone: 20 launches back to back between two HIP events on their
+    # stream (the per-kernel figures above carry the event commands around every launch)
+    alone = {"wta_pass": kms[7], "aht_pass": kms[8]}
+    log("[bench] pass kernels, back-to-back launches, ms:", {a: round(b, 4) for a, b in alone.items()})
+    timed = {a: (alone[a] if alone[a] > 0 else kern[a]) for a in alone}
+    dom = max(timed, key=lambda x: timed[x])
     bytes_a = m * n * 4          # one pass reads every element of A once: 4 B per element
-    ach = bytes_a / (kern[dom] * 1e-3) / 1e9
+    ach = bytes_a / (timed[dom] * 1e-3) / 1e9
     gbs_iter = 2 * bytes_a / (ms_step * 1e-3) / 1e9
     out = {
         "metric": "MU iterations/s (dense fp32, resident A)", "value": 1e3 / ms_step, "unit": "iterations/s",
@@ -90,8 +95,8 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
         "config": {"workload": f"{tag}: dense fp32 A {m}x{n} resident, planted rank {rank} x U[0.95,1.05), k={k}, "
                                "one step = one MU iteration (2 reads of A)", "m": m, "n": n, "k": k},
         "gbs_over_A": gbs_iter, "frac_hbm_peak_over_A": gbs_iter / HBM_PEAK_GBS,
-        "kernel_ms": kern,
-        "roofline": {"bound": "hbm", "kernel": dom, "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "kernel_ms": kern, "pass_kernel_ms_back_to_back": alone,
+        "roofline": {"bound": "hbm", "kernel": dom, "kernel_ms": timed[dom], "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": ach / HBM_PEAK_GBS,
                      "traffic": C2_PASS_TRAFFIC_BYTES if (m, n, k, bool(kms[6])) == (32768, 16384, 32, True) else None,
                      "algorithmic_bytes_per_launch": bytes_a},

@@ -80,13 +80,16 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
 /*
  * nmf_mu_dense with timing: the same launches on `stream`, with a HIP event
  * recorded between them; synchronises `stream` before returning.  On return
- * kernel_ms[0..5] (HOST memory, 7 floats) hold the average milliseconds per
+ * kernel_ms[0..5] (HOST memory, 9 floats) hold the average milliseconds per
  * launch of the kernels of one iteration, in launch order:
  *   [0] W^T W   [1] W^T A pass   [2] H update   [3] H H^T
  *   [4] A H^T pass (on the mirrored copy A^T, or the direct kernel with the W
  *       update fused)   [5] W update (0 for the direct kernel)
  * and kernel_ms[6] is 1 if the mirrored plan ran (see nmf_mu_workspace_bytes),
- * else 0.  1 <= iters <= 4096.
+ * else 0.  kernel_ms[7] and [8]: milliseconds per launch of the W^T A pass and
+ * (mirrored plan only, else 0) of the pass on A^T, from 20 launches back to
+ * back between two events after the run, i.e. without the event commands that
+ * surround every kernel in [0..5].  1 <= iters <= 4096.
  */
 int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k,
                          float *W, float *H, int32_t iters, float eps, void *stream,

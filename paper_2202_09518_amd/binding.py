@@ -107,8 +107,9 @@ def nmf_mu_dense(A, m, n, k, W, H, iters, eps, stream=None) -> None:
 
 
 def nmf_mu_dense_profile(A, m, n, k, W, H, iters, eps, stream=None):
-    """Returns [six average kernel times in ms (launch order of one iteration), mirrored flag]."""
-    ms = (ctypes.c_float * 7)()
+    """Returns [six average kernel times in ms (launch order of one iteration), mirrored flag,
+    ms per launch of the pass over A and of the pass over A^T launched back to back]."""
+    ms = (ctypes.c_float * 9)()
     _check(lib().nmf_mu_dense_profile(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
                                       _dev(H, torch.float32, "H"), iters, eps, _stream(stream), ms))
     return list(ms)

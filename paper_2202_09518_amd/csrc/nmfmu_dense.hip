@@ -33,6 +33,46 @@ __device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c)
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
+// ---- exact fp32 products on the bf16 matrix cores ---------------------------------
+// A float x is cut into three pieces h + m + l = x, each with at most 8
+// significant bits (a bf16 holds 8): h = x truncated to its top 8 bits,
+// m = (x - h) truncated likewise, l = the rest.  Both subtractions are exact,
+// so the sum of the pieces is x bit for bit (for |x| >= 2^-110; below that the
+// last piece can fall under the bf16 range and is dropped by the hardware).  A
+// product of two pieces has at most 16 significant bits and is exact in the
+// fp32 accumulator, so the nine piece products of x y add up to the exact x y:
+// v_mfma_f32_32x32x16_bf16 on pieces computes the same sums of products as
+// v_mfma_f32_32x32x2_f32 on the floats, with the roundings of the running sums
+// only, at a quarter of the matrix-core time per product.
+//
+// Lane layout of v_mfma_f32_32x32x16_bf16: A_op (32 x 16): lane l holds
+// A_op[l % 32][8 (l / 32) .. 8 (l / 32) + 7]; B_op (16 x 32): lane l holds
+// B_op[8 (l / 32) .. + 7][l % 32]; D as for the fp32 instruction.
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ f32x16 mfma_bf16(u32x4 a, u32x4 b, f32x16 c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+// Bit patterns of the three pieces as floats (their low 16 bits are zero, or
+// dropped by pack2: the top 16 bits are the bf16).
+__device__ __forceinline__ void split3(float x, unsigned &h, unsigned &m, unsigned &l)
+{
+    h = __float_as_uint(x) & 0xffff0000u;
+    const float r = x - __uint_as_float(h);
+    m = __float_as_uint(r) & 0xffff0000u;
+    l = __float_as_uint(r - __uint_as_float(m));
+}
+
+// Two bf16 in one register: `even` in the low half, `odd` in the high half.
+__device__ __forceinline__ unsigned pack2(unsigned even, unsigned odd)
+{
+    return __builtin_amdgcn_perm(odd, even, 0x07060302u);
+}
+
 // Row of the 32 x 32 accumulator held in register v of a lane in half `half`.
 __device__ __forceinline__ int acc_row(int v, int half) { return (v & 3) + 4 * half + 8 * (v >> 2); }
 
@@ -271,6 +311,137 @@ __global__ __launch_bounds__(64 * kWtaWaves, OCC) void wta_pass_kernel(const flo
 }
 
 // ---------------------------------------------------------------------------
+// Piece planes of a factor X (rows x k, row-major), the A_op of the pass below:
+// planes[(g * 3 + p) * 32 + c] = the eight bf16 p-th pieces (p = 0: h, 1: m, 2: l)
+// of X[8 g .. 8 g + 7][c], c < 32; rows beyond `rows` and factors beyond k are zero.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void split_planes_kernel(const float *__restrict__ X, int64_t rows,
+                                                           int k, u32x4 *__restrict__ planes)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t g = t >> 5;
+    const int c = (int)(t & 31);
+    if (g * 8 >= rows) return;
+    u32x4 o[3];
+#pragma unroll
+    for (int pr = 0; pr < 4; ++pr) {
+        unsigned h[2], m[2], l[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int64_t row = g * 8 + 2 * pr + e;
+            const float x = (row < rows && c < k) ? X[row * k + c] : 0.f;
+            split3(x, h[e], m[e], l[e]);
+        }
+        o[0][pr] = pack2(h[0], h[1]);
+        o[1][pr] = pack2(m[0], m[1]);
+        o[2][pr] = pack2(l[0], l[1]);
+    }
+#pragma unroll
+    for (int pl = 0; pl < 3; ++pl) planes[(g * 3 + pl) * 32 + c] = o[pl];
+}
+
+// ---------------------------------------------------------------------------
+// W^T A pass for k <= 32 with exact products on the bf16 matrix cores (see
+// split3 above).  Geometry as wta_pass_kernel: 4 waves on a 128-column slab and
+// one row split, lane = 4 consecutive columns; but a wave takes 16 rows per step
+// (half-wave = 8 consecutive rows, the reduction depth of one instruction), loads
+// them with eight 16-byte loads per lane, cuts each element into its pieces in
+// registers and reads the pieces of W ready-made (planes, 3 x 16 bytes per lane
+// and step).  Per column tile the nine piece products are accumulated smallest
+// first.  r0 of every split is a multiple of 16 (rps is), so a half-wave's rows
+// are one 8-row group of the planes.  Two waves per SIMD (256 registers each).
+// ---------------------------------------------------------------------------
+template <bool VEC>
+__global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_kernel(
+    const float *__restrict__ A, const u32x4 *__restrict__ planes, float *__restrict__ ppart,
+    int64_t rows, int64_t n, int k, int64_t rps, int accumulate)
+{
+    constexpr int NW = kWtaWaves;
+    constexpr int LD = 132;
+    __shared__ float red[32 * LD];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int jj = lane & 31, half = lane >> 5;
+    const int64_t j0 = (int64_t)blockIdx.x * kWtaCols;
+    const int64_t col = j0 + 4 * jj;
+    const int64_t r0 = (int64_t)blockIdx.y * rps;
+    const int64_t r1 = (r0 + rps < rows) ? r0 + rps : rows;
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = f32x16{0};
+
+    struct Stage {
+        f32x4 a[8];
+        u32x4 wt[3];
+    };
+    auto load_stage = [&](Stage &s, int64_t ibase) {
+        const int64_t rb = ibase + 8 * half;
+#pragma unroll
+        for (int r = 0; r < 8; ++r) s.a[r] = load4<VEC>(A, n, rb + r, col, rb + r < r1);
+        // rows at or beyond r1 contribute nothing because their A elements read as zero
+        const int64_t g = rb >> 3;
+        const bool okg = rb < r1;
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) s.wt[pl] = planes[okg ? (g * 3 + pl) * 32 + jj : 0];
+    };
+    const int64_t step = 16 * NW;
+    Stage cur, nxt;
+    int64_t i = r0 + 16 * w;
+    load_stage(cur, i);
+    for (; i < r1; i += step) {
+        load_stage(nxt, i + step);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32x4 at[3];
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                unsigned h0, m0, l0, h1, m1, l1;
+                split3(cur.a[2 * pr][q], h0, m0, l0);
+                split3(cur.a[2 * pr + 1][q], h1, m1, l1);
+                at[0][pr] = pack2(h0, h1);
+                at[1][pr] = pack2(m0, m1);
+                at[2][pr] = pack2(l0, l1);
+            }
+            acc[q] = mfma_bf16(cur.wt[2], at[2], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[2], at[1], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[1], at[2], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[2], at[0], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[1], at[1], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[0], at[2], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[1], at[0], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[0], at[1], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[0], at[0], acc[q]);
+        }
+        cur = nxt;
+    }
+
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int idx = acc_row(v, half) * LD + q * 32 + jj;
+                    if (ww == 0) red[idx] = acc[q][v];
+                    else red[idx] += acc[q][v];
+                }
+        }
+        __syncthreads();
+    }
+    float *dst = ppart + (int64_t)blockIdx.y * k * n;
+    for (int e = tid; e < k * kWtaCols; e += 64 * NW) {
+        const int c = e >> 7, x = e & 127;
+        const int64_t cj = j0 + x;
+        if (cj < n) {
+            float val = red[c * LD + (x & 3) * 32 + (x >> 2)];
+            float *p = dst + (int64_t)c * n + cj;
+            if (accumulate) val += *p;
+            *p = val;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Factor update ("finisher").  For X (k x len), partials of its numerator and
 // the Gram matrix G of the other factor:
 //     X[c][j] <- X[c][j] * (sum_s part[s][c][j]) / (sum_d G[c][d] X[d][j] + eps).
@@ -295,7 +466,8 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                                                             int splits,
                                                             const float *__restrict__ Gfull,
                                                             const float *__restrict__ gin, int nbin,
-                                                            float *__restrict__ gout, int k,
+                                                            float *__restrict__ gout,
+                                                            u32x4 *__restrict__ planes, int k,
                                                             int64_t len, float eps, BlockMap bm)
 {
     constexpr int NW = 8, KT = KP / 32 > 0 ? KP / 32 : 1, NC = (KP + 7) / 8, LD = KP + 1;
@@ -416,6 +588,28 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
             for (int e = tid; e < 64 * k; e += 64 * NW) {
                 const int jj = e / k, c = e % k;
                 if (ch * 64 + jj < len) Xt[(ch * 64 + jj) * k + c] = Ts[jj * LDT + c];
+            }
+        }
+        if (KP <= 32 && planes && tid < 256) {
+            // bf16 piece planes of the new X^T rows of this chunk (layout of split_planes_kernel)
+            const int gl = tid >> 5, c = tid & 31;
+            const int64_t grow = ch * 8 + gl;
+            if (grow * 8 < len) {
+                u32x4 o[3];
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) {
+                    unsigned hh[2], mm[2], ll[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) {
+                        const float x = (c < k) ? Ts[(8 * gl + 2 * pr + e) * LDT + c] : 0.f;
+                        split3(x, hh[e], mm[e], ll[e]);
+                    }
+                    o[0][pr] = pack2(hh[0], hh[1]);
+                    o[1][pr] = pack2(mm[0], mm[1]);
+                    o[2][pr] = pack2(ll[0], ll[1]);
+                }
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) planes[(grow * 3 + pl) * 32 + c] = o[pl];
             }
         }
         if (gout) {
@@ -700,11 +894,12 @@ static inline bool vec_ok(const void *p, int64_t ld)
 
 int wta_splits(int64_t rows, int64_t n, int k)
 {
-    // Enough workgroups to fill the chip once at the kernel's occupancy (4 groups per
-    // compute unit for k <= 32, 2 above), but long row ranges per group: every split
-    // costs a k x n partial result written and read again.
+    // Enough workgroups to fill the chip once at the kernels' occupancy (2 groups per
+    // compute unit), but long row ranges per group: every split costs a k x n partial
+    // result written and read again.
+    (void)k;
     const int64_t slabs = (n + kWtaCols - 1) / kWtaCols;
-    const int64_t target = (k <= 32) ? 1024 : 512;
+    const int64_t target = 512;
     int64_t s = (target + slabs - 1) / slabs;
     const int64_t max_by_rows = (rows + 255) / 256;   // at least 256 rows per split
     if (s > max_by_rows) s = max_by_rows;
@@ -716,7 +911,7 @@ int wta_splits(int64_t rows, int64_t n, int k)
 int64_t wta_rows_per_split(int64_t rows, int splits)
 {
     int64_t rps = (rows + splits - 1) / splits;
-    return (rps + 1) & ~(int64_t)1;   // even, so that a row pair never straddles a split
+    return (rps + 15) & ~(int64_t)15;   // whole 16-row steps of a wave (and whole row pairs)
 }
 
 static int gram_blocks(int64_t len, int per_block)
@@ -752,7 +947,7 @@ template <int KT>
 static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *W,
                          float *ppart, int64_t rows, int64_t n, int k, int64_t rps, int acc)
 {
-    constexpr int U = (KT == 1) ? 3 : 5, OCC = (KT == 1) ? 4 : 2;
+    constexpr int U = 5, OCC = 2;
     const dim3 block(64 * kWtaWaves);
     if (vec)
         hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, true>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);
@@ -760,14 +955,40 @@ static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, co
         hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, false>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);
 }
 
+size_t planes_bytes(int64_t rows) { return (size_t)((rows + 7) / 8) * 3 * 32 * 16; }
+
+hipError_t launch_split_planes(const float *X, int64_t rows, int k, void *planes, hipStream_t st)
+{
+    if (!wta_uses_planes(k)) return hipSuccess;
+    const int64_t threads = ((rows + 7) / 8) * 32;
+    hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, X,
+                       rows, k, static_cast<u32x4 *>(planes));
+    return hipGetLastError();
+}
+
 hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
-                           float *ppart, int splits, int64_t rps, bool accumulate, hipStream_t st)
+                           void *planes, bool planes_ready, float *ppart, int splits, int64_t rps,
+                           bool accumulate, hipStream_t st)
 {
     dim3 grid((unsigned)((n + kWtaCols - 1) / kWtaCols), (unsigned)splits);
     const bool vec = vec_ok(A, n);
     const int acc = accumulate ? 1 : 0;
+    if (rps % 16) return hipErrorInvalidValue;
     switch (k_tiles(k)) {
-    case 1: wta_dispatch<1>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc); break;
+    case 1: {
+        if (!planes) return hipErrorInvalidValue;
+        if (!planes_ready) {
+            hipError_t e = launch_split_planes(W, rows, k, planes, st);
+            if (e != hipSuccess) return e;
+        }
+        const u32x4 *pl = static_cast<const u32x4 *>(planes);
+        const dim3 block(64 * kWtaWaves);
+        if (vec)
+            hipLaunchKernelGGL((wta_pass_split_kernel<true>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc);
+        else
+            hipLaunchKernelGGL((wta_pass_split_kernel<false>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc);
+        break;
+    }
     case 2: wta_dispatch<2>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc); break;
     default: return hipErrorInvalidValue;
     }
@@ -793,8 +1014,10 @@ int factor_update_blocks(int64_t len)
 
 hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
                                 const float *Gfull, const float *gin, int nbin, float *gout, int k,
-                                int64_t len, float eps, hipStream_t st, const BlockMap *map)
+                                int64_t len, float eps, hipStream_t st, const BlockMap *map,
+                                void *planes)
 {
+    u32x4 *pl = wta_uses_planes(k) ? static_cast<u32x4 *>(planes) : nullptr;
     BlockMap bm;
     if (map) bm = *map;
     else bm.on = 0;
@@ -803,11 +1026,11 @@ hipError_t launch_factor_update(float *X, float *Xt, const float *part, int spli
     if (blocks > 65535) blocks = 65535;
     const dim3 grid((unsigned)blocks), block(512);
     if (k <= 8)
-        hipLaunchKernelGGL((factor_update_kernel<8>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps, bm);
+        hipLaunchKernelGGL((factor_update_kernel<8>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, k, len, eps, bm);
     else if (k <= 32)
-        hipLaunchKernelGGL((factor_update_kernel<32>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps, bm);
+        hipLaunchKernelGGL((factor_update_kernel<32>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, k, len, eps, bm);
     else
-        hipLaunchKernelGGL((factor_update_kernel<64>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, k, len, eps, bm);
+        hipLaunchKernelGGL((factor_update_kernel<64>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, k, len, eps, bm);
     return hipGetLastError();
 }
 

@@ -39,20 +39,28 @@ hipError_t launch_gram_w(const float *X, int64_t rows, int k, float *G, float *g
 // G (k x k, ld k) = X X^T for X k x cols (row-major, ld cols).
 hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *gpart,
                          unsigned *counters, hipStream_t st);
-// ppart[s] (+)= W[r0_s:r1_s]^T A[r0_s:r1_s] for each row split s (k x n each).
+// Ranks whose W^T A pass reads its factor as bf16 piece planes (planes_bytes(rows) bytes,
+// written by launch_split_planes from the rows x k factor) instead of the floats.
+inline bool wta_uses_planes(int k) { return k <= 32; }
+size_t planes_bytes(int64_t rows);
+hipError_t launch_split_planes(const float *X, int64_t rows, int k, void *planes, hipStream_t st);
+// ppart[s] (+)= W[r0_s:r1_s]^T A[r0_s:r1_s] for each row split s (k x n each).  `planes`:
+// scratch of planes_bytes(rows) bytes (unused unless wta_uses_planes(k)); with planes_ready it
+// already holds the planes of W, otherwise they are produced first.
 hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
-                           float *ppart, int splits, int64_t rows_per_split, bool accumulate,
-                           hipStream_t st);
+                           void *planes, bool planes_ready, float *ppart, int splits,
+                           int64_t rows_per_split, bool accumulate, hipStream_t st);
 // P[e] = sum_s ppart[s][e], e < count.
 hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
                                hipStream_t st);
 // X (k x len) <- X * (sum_s part[s]) / (G X + eps), in place.  G is given complete (Gfull, ld k)
 // or as nbin partial tiles (gin).  Optional: Xt (len x k) = new X^T; gout = partial Gram tiles
-// of the new X, one set per block (factor_update_blocks(len) blocks).
+// of the new X, one set per block (factor_update_blocks(len) blocks); planes = the bf16 piece
+// planes of the new X^T (planes_bytes(len) bytes; written only if wta_uses_planes(k)).
 hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
                                 const float *Gfull, const float *gin, int nbin, float *gout, int k,
                                 int64_t len, float eps, hipStream_t st,
-                                const BlockMap *map = nullptr);
+                                const BlockMap *map = nullptr, void *planes = nullptr);
 int factor_update_blocks(int64_t len);
 // G (k x k, ld k) = sum of nb sets of partial tiles.
 hipError_t launch_gram_sum(const float *gpart, int nb, int k, float *G, hipStream_t st);

@@ -290,8 +290,14 @@ def test_small_plan_dense_one_iteration(m, n, k):
 
 def test_profile_entry_reports_plan_and_times():
     A, W, H = case(512, 384, 8, 33)
-    ms = nmf.nmf_mu_dense_profile(dev(A), 512, 384, 8, dev(W), dev(H), 3, EPS)
-    assert len(ms) == 7 and ms[6] == 1.0 and all(x >= 0 for x in ms[:6]) and ms[1] > 0 and ms[4] > 0
+    Wd, Hd = dev(W), dev(H)
+    ms = nmf.nmf_mu_dense_profile(dev(A), 512, 384, 8, Wd, Hd, 3, EPS)
+    assert len(ms) == 9 and ms[6] == 1.0 and all(x >= 0 for x in ms[:6]) and ms[1] > 0 and ms[4] > 0
+    assert ms[7] > 0 and ms[8] > 0
+    # the timing launches leave the result alone: same bits as the plain entry point
+    Wg, Hg = run_dense(A, W, H, 3)
+    np.testing.assert_array_equal(host(Wd), Wg)
+    np.testing.assert_array_equal(host(Hd), Hg)
 
 
 def test_ooc_pageable_host_memory_and_config1():
