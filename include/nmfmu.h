@@ -202,6 +202,19 @@ int nmf_mu_release(void);
  * entries to a whole workgroup instead.  Asynchronous on `stream`. */
 int nmf_csr_partition(const int64_t *rowptr, int64_t m, int32_t nparts, int64_t *part, void *stream);
 
+/* The operand encoding of the W^T A pass for k <= 32.  The products of
+ * Algorithms 2-5 (W^T A, and A H^T as the same product on the transposes) are
+ * formed on the bf16 matrix cores from exact pieces: a float x is cut into
+ * x = h + m + l, h = x with its significand truncated to 8 bits, m = x - h
+ * truncated likewise, l = x - h - m (each piece is a bf16, the sum is x bit
+ * for bit for |x| >= 2^-110); all nine piece products of a term are
+ * accumulated in fp32.  This call writes the pieces of X (rows x k, row-major,
+ * device, k <= 32) as the kernels read them: for row group g = row / 8, piece
+ * p (0: h, 1: m, 2: l) and factor c < 32, the eight bf16 of rows 8g .. 8g+7 at
+ * planes[((g * 3 + p) * 32 + c) * 8 ..]; rows >= `rows` and factors >= k are
+ * zero.  `planes`: device, ceil(rows / 8) * 768 uint16.  Asynchronous. */
+int nmf_split_planes(const float *X, int64_t rows, int32_t k, uint16_t *planes, void *stream);
+
 /* Column-ordered copy of a CSR matrix, the structure nmf_mu_csr derives for its
  * W^T A product: colptr int64[n + 1], rowidx int32[nnz], cvals float[nnz] (all
  * device, caller-allocated).  Entries of a column keep the order in which the

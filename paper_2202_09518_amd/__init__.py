@@ -9,5 +9,5 @@ from .binding import (  # noqa: F401
     nmf_status_string, nmf_last_error,
     nmf_mu_dense, nmf_mu_dense_profile, nmf_residual_dense, nmf_mu_dense_tol, nmf_mu_csr, nmf_mu_ooc, nmf_mu_dense_batched,
     nmf_mu_workspace_bytes, nmf_mu_set_workspace, nmf_mu_release,
-    nmf_csr_partition, nmf_csr_to_csc, nmf_gram_w, nmf_wta_dense, nmf_h_update, nmf_aht_w_update_dense,
+    nmf_csr_partition, nmf_split_planes, nmf_csr_to_csc, nmf_gram_w, nmf_wta_dense, nmf_h_update, nmf_aht_w_update_dense,
 )

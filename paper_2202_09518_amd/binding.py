@@ -19,7 +19,7 @@ EXPORTS = [
     "nmf_status_string", "nmf_last_error",
     "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
-    "nmf_csr_partition", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
+    "nmf_csr_partition", "nmf_split_planes", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
 
 NMF_OK, NMF_EINVAL, NMF_ENOMEM, NMF_EHIP, NMF_EUNSUPPORTED = range(5)
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_mu_set_workspace.argtypes = [vp, ctypes.c_size_t]
     L.nmf_mu_release.argtypes = []
     L.nmf_csr_partition.argtypes = [vp, i64, i32, vp, vp]
+    L.nmf_split_planes.argtypes = [vp, i64, i32, vp, vp]
     L.nmf_csr_to_csc.argtypes = [vp, vp, vp, i64, i64, i64, vp, vp, vp, vp]
     L.nmf_gram_w.argtypes = [vp, i64, i32, vp, vp]
     L.nmf_wta_dense.argtypes = [vp, i64, i64, i32, vp, vp, vp]
@@ -176,6 +177,12 @@ def nmf_mu_release() -> None:
 def nmf_csr_partition(rowptr, m, nparts, part, stream=None) -> None:
     _check(lib().nmf_csr_partition(_dev(rowptr, torch.int64, "rowptr"), m, nparts,
                                    _dev(part, torch.int64, "part"), _stream(stream)))
+
+
+def nmf_split_planes(X, rows, k, planes, stream=None) -> None:
+    """planes: int16 device tensor of ceil(rows / 8) * 768 elements (bf16 bit patterns)."""
+    _check(lib().nmf_split_planes(_dev(X, torch.float32, "X"), rows, k, _dev(planes, torch.int16, "planes"),
+                                  _stream(stream)))
 
 
 def nmf_csr_to_csc(rowptr, colidx, vals, m, n, nnz, colptr, rowidx, cvals, stream=None) -> None:

@@ -737,6 +737,16 @@ int nmf_csr_partition(const int64_t *rowptr, int64_t m, int32_t nparts, int64_t 
     return NMF_OK;
 }
 
+int nmf_split_planes(const float *X, int64_t rows, int32_t k, uint16_t *planes, void *stream)
+{
+    if (!X || !planes) return fail(NMF_EINVAL, "null pointer%s");
+    if (rows < 1 || k < 1) return fail(NMF_EINVAL, "bad size%s");
+    if (!wta_uses_planes(k)) return fail(NMF_EUNSUPPORTED, "piece planes are used for k <= 32 only%s");
+    if (reinterpret_cast<uintptr_t>(planes) % 16) return fail(NMF_EINVAL, "planes must be 16-byte aligned%s");
+    NMF_HIP(launch_split_planes(X, rows, k, planes, static_cast<hipStream_t>(stream)));
+    return NMF_OK;
+}
+
 int nmf_csr_to_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
                    int64_t n, int64_t nnz, int64_t *colptr, int32_t *rowidx, float *cvals,
                    void *stream)

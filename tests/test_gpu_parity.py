@@ -185,6 +185,42 @@ def test_dense_on_a_side_stream_and_unaligned_views():
     check(host(Wd), host(Hd), Wr, Hr, 2e-5)
 
 
+# ---- operand encoding of the k <= 32 pass (bit-exact) ---------------------------------
+
+def bf16_bits_to_f64(u16):
+    return (u16.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+@pytest.mark.parametrize("rows,k", [(1, 1), (8, 32), (13, 5), (1000, 32), (4099, 17)])
+def test_split_planes_encoding_is_exact(rows, k):
+    """The three bf16 pieces of every factor entry add up to the entry bit for bit,
+    each piece is the truncation the header states, the layout is the stated one
+    and the padding is zero (host recomputation with integer masks)."""
+    r = np.random.default_rng(rows * 100 + k)
+    X = (r.random((rows, k), dtype=np.float32) * np.float32(10.0) ** r.integers(-20, 20, (rows, k))).astype(np.float32)
+    X[0, 0] = 0.0
+    X[rows // 2, k // 2] = np.float32(1.0)          # one piece only
+    X[rows - 1, k - 1] = np.float32(3.0e38)
+    groups = (rows + 7) // 8
+    planes = torch.full((groups * 768,), -1, dtype=torch.int16, device="cuda")
+    nmf.nmf_split_planes(dev(X), rows, k, planes)
+    torch.cuda.synchronize()
+    P = planes.cpu().numpy().view(np.uint16).reshape(groups, 3, 32, 8)
+    # host: truncation by masking the low 16 bits, exact float32 subtractions
+    Xp = np.zeros((groups * 8, 32), dtype=np.float32)
+    Xp[:rows, :k] = X
+    h = (Xp.view(np.uint32) & np.uint32(0xffff0000)).view(np.float32)
+    r1 = Xp - h
+    m = (r1.view(np.uint32) & np.uint32(0xffff0000)).view(np.float32)
+    l = r1 - m
+    assert ((l.view(np.uint32) & np.uint32(0xffff)) == 0).all()      # the last piece is a bf16 already
+    want = np.stack([(x.view(np.uint32) >> 16).astype(np.uint16).reshape(groups, 8, 32).transpose(0, 2, 1)
+                     for x in (h, m, l)], axis=1)
+    np.testing.assert_array_equal(P, want)
+    total = bf16_bits_to_f64(P[:, 0]) + bf16_bits_to_f64(P[:, 1]) + bf16_bits_to_f64(P[:, 2])
+    np.testing.assert_array_equal(total.transpose(0, 2, 1).reshape(groups * 8, 32), Xp.astype(np.float64))
+
+
 # ---- objective and tolerance-driven run --------------------------------------------
 
 @pytest.mark.parametrize("m,n,k", SHAPES + [(4096, 2048, 32)])
