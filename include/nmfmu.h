@@ -35,7 +35,8 @@
  *   - Every function returns a status code and never throws, exits or prints.
  *     Entries of A, W, H are not inspected: negative or non-finite input gives
  *     an undefined (but non-faulting) result.  iters == 0 is a successful
- *     no-op.  Supported rank: 1 <= k <= NMF_MU_MAX_K.
+ *     no-op.  Supported rank: 1 <= k <= NMF_MU_MAX_K; nmf_mu_dense, nmf_mu_ooc
+ *     and nmf_mu_ooc_hostw go up to NMF_MU_MAX_K_SLICED.
  */
 #ifndef NMFMU_H
 #define NMFMU_H
@@ -52,10 +53,11 @@ enum {
     NMF_EINVAL = 1,       /* null pointer, non-positive size, bad eps/iters/batch */
     NMF_ENOMEM = 2,       /* workspace or staging buffers do not fit */
     NMF_EHIP = 3,         /* a HIP runtime call failed; see nmf_last_error() */
-    NMF_EUNSUPPORTED = 4  /* k > NMF_MU_MAX_K */
+    NMF_EUNSUPPORTED = 4  /* rank above what the entry point supports */
 };
 
-#define NMF_MU_MAX_K 64
+#define NMF_MU_MAX_K 64           /* ranks served by the fused kernels */
+#define NMF_MU_MAX_K_SLICED 1024  /* ranks served 32 factor columns at a time (see nmf_mu_dense) */
 
 /* Static, human-readable name of a status code. */
 const char *nmf_status_string(int status);
@@ -73,6 +75,13 @@ const char *nmf_last_error(void);
  * library transposes A once per call and streams A^T for the A H^T product
  * (both passes then read memory in row order); otherwise it runs a direct
  * A H^T kernel on A.  Both give the same iteration; low-order bits differ.
+ * Ranks NMF_MU_MAX_K < k <= NMF_MU_MAX_K_SLICED run the same iteration with every
+ * product written as F^T X (a reduction over the rows of two row-major
+ * matrices) and computed 32 factor columns of F at a time by the k <= 32 pass
+ * kernel: W^T A, W^T W, (W^T W) H, and the same three on the transposes A^T,
+ * H^T, W^T for the W update, followed by the element-wise update.  A is read
+ * ceil(k / 32) times per product; the workspace holds A^T, W^T, H^T and two
+ * k x max(m, n) arrays (nmf_mu_workspace_bytes kind 5), else NMF_ENOMEM.
  */
 int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
                  float *W, float *H, int32_t iters, float eps, void *stream);
@@ -150,10 +159,33 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
  *                        library uses min(3, what fits) staging slots of
  *                        batch_rows x n floats and fails with NMF_ENOMEM if not
  *                        even one fits
+ * Ranks above NMF_MU_MAX_K take the pipeline of nmf_mu_ooc_hostw with W kept on the device.
  */
 int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k,
                float *W, float *H, int32_t iters, float eps,
                int64_t batch_rows, int64_t device_budget_bytes, void *stream);
+
+/*
+ * Out-of-memory dense MU with W in host memory as well (Algorithm 5 as printed:
+ * per batch, W_b and A_b go to the device, W_b is updated and copied back, and
+ * W_b^T A_b, W_b^T W_b are accumulated for the H update; section 4.4 is the
+ * benchmark).  Same sweep order as nmf_mu_ooc.  Any rank up to
+ * NMF_MU_MAX_K_SLICED; all products go through the rank-sliced engine described
+ * at nmf_mu_dense, the A H^T of a batch on a transposed copy of the batch.
+ *   A_host, W_host  host (pinned for overlap), m x n and m x k; W_host is
+ *                   updated in place and complete once `stream` has been
+ *                   synchronised
+ *   H               device, k x n, in/out
+ *   slots           1 .. 16 staging slots of (batch_rows x n + batch_rows x k)
+ *                   floats: the stand-in for the paper's stream-queue size q_s;
+ *                   uploads run `slots` - 1 batches ahead of the compute
+ *                   stream, downloads of W_b on a third stream
+ *   device_bytes_host  optional (host): receives the device memory the call
+ *                   uses (workspace + staging), for the O(p n q_s) memory model
+ */
+int nmf_mu_ooc_hostw(const float *A_host, float *W_host, int64_t m, int64_t n, int32_t k,
+                     float *H, int32_t iters, float eps, int64_t batch_rows, int32_t slots,
+                     void *stream, size_t *device_bytes_host);
 
 /*
  * Ensemble of independent resident dense runs of one shape (the perturbed
@@ -176,8 +208,10 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
  * library keeps a transposed copy of A, so this is about m*n*4 bytes plus the
  * partial sums), 4 dense (small plan: partial sums only; used automatically
  * when the fast plan's workspace cannot be had), 1 csr, 2 ooc (excluding the
- * staging slots), 3 batched (enough for any mix of ranks; k is only checked).
- * 0 on invalid arguments.
+ * staging slots), 3 batched (enough for any mix of ranks; k is only checked),
+ * 5 dense with k > NMF_MU_MAX_K (rank-sliced), 6 the rank-sliced out-of-memory
+ * pipeline (nmf_mu_ooc_hostw, and nmf_mu_ooc above NMF_MU_MAX_K; excluding the
+ * staging slots).  0 on invalid arguments.
  */
 size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz,
                               int32_t k, int64_t batch_rows);

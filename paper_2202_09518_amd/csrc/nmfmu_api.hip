@@ -44,6 +44,11 @@ struct State {
     hipEvent_t ev_copied[3] = {nullptr, nullptr, nullptr};
     hipEvent_t ev_freed[3] = {nullptr, nullptr, nullptr};
     hipEvent_t ev_entry = nullptr;
+    // rank-sliced out-of-memory path: up to kMaxSlots staging slots, factor rows copied back
+    void *sl_stage = nullptr;
+    size_t sl_stage_bytes = 0;
+    hipStream_t back_stream = nullptr;
+    hipEvent_t sl_copied[16] = {}, sl_done[16] = {}, sl_freed[16] = {};
 };
 State g;
 
@@ -111,11 +116,11 @@ int ensure_workspace(size_t need, void **out)
 }
 
 int check_common(const void *a, const void *w, const void *h, int64_t m, int64_t n, int32_t k,
-                 int32_t iters, float eps)
+                 int32_t iters, float eps, int32_t kmax = NMF_MU_MAX_K)
 {
     if (!a || !w || !h) return fail(NMF_EINVAL, "null pointer%s");
     if (m < 1 || n < 1 || k < 1) return fail(NMF_EINVAL, "m, n, k must be >= 1%s");
-    if (k > NMF_MU_MAX_K) return fail(NMF_EUNSUPPORTED, "k exceeds NMF_MU_MAX_K%s");
+    if (k > kmax) return fail(NMF_EUNSUPPORTED, "k exceeds the rank this entry point supports%s");
     if (iters < 0) return fail(NMF_EINVAL, "iters must be >= 0%s");
     if (!(eps >= 0.f) || !std::isfinite(eps)) return fail(NMF_EINVAL, "eps must be finite and >= 0%s");
     if (m > (int64_t)1 << 40 || n > (int64_t)1 << 31) return fail(NMF_EINVAL, "matrix too large%s");
@@ -287,6 +292,236 @@ int build_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, i
     return NMF_OK;
 }
 
+// ---- rank-sliced engine (ranks above NMF_MU_MAX_K, and the host-resident-W pipeline) ----
+// Every product of the iteration is written as F^T X with F (rows x k) and X (rows x cols)
+// row-major, i.e. a reduction over the rows of both, and computed 32 factor columns at a
+// time by the k <= 32 pass kernel on the piece planes of that slice of F:
+//   W^T A, W^T W                      F = W,  X = A or W
+//   (W^T W) H                         F = W^T W (symmetric), X = H
+//   A H^T, H H^T, W (H H^T)           the same three on the transposes A^T, H^T, W^T
+// followed by the element-wise update.  X is read once per slice.
+struct Sliced {
+    void *planes;     // planes_bytes(max rows of any F)
+    float *ppart;     // row-split partials of one slice: splits x 32 x max cols
+    size_t planes_cap, ppart_elems;
+};
+
+int sliced_ftx(const Sliced &e, const float *F, int64_t rows, int k, const float *X, int64_t cols,
+               float *out, bool accumulate, hipStream_t st)
+{
+    const int splits = wta_splits(rows, cols, 32);
+    const int64_t rps = wta_rows_per_split(rows, splits);
+    if ((size_t)splits * 32 * (size_t)cols > e.ppart_elems || planes_bytes(rows) > e.planes_cap)
+        return fail(NMF_EHIP, "internal: sliced scratch too small%s");
+    for (int c0 = 0; c0 < k; c0 += 32) {
+        const int kc = (k - c0 < 32) ? k - c0 : 32;
+        NMF_HIP(launch_split_planes_slice(F, rows, k, c0, kc, e.planes, st));
+        NMF_HIP(launch_wta_pass(X, rows, cols, kc, nullptr, e.planes, true, e.ppart, splits, rps, false, st));
+        NMF_HIP(launch_sum_partials(e.ppart, splits, (int64_t)kc * cols, out + (int64_t)c0 * cols, st, accumulate));
+    }
+    return NMF_OK;
+}
+
+// Upper bound on splits x 32 x cols over every X with at most `cols` columns: the split count is
+// at most 32 and at most 512 / slabs + 1 with cols <= 128 slabs.
+size_t sliced_ppart_elems(int64_t cols)
+{
+    const int64_t a = 32 * cols, b = 65536 + cols;
+    return (size_t)32 * (size_t)(a < b ? a : b);
+}
+
+// Resident run of rank k > NMF_MU_MAX_K.
+struct SlicedDense {
+    Sliced e;
+    float *At, *Wt, *Ht, *num, *den, *gw, *gh;
+};
+
+template <class T> T max3(T a, T b, T c) { return a > b ? (a > c ? a : c) : (b > c ? b : c); }
+
+SlicedDense carve_sliced_dense(void *ws, int64_t m, int64_t n, int k, size_t *bytes)
+{
+    Carve cv(ws);
+    SlicedDense p;
+    cv.take<unsigned>(64);
+    const int64_t big = m > n ? m : n;
+    p.e.planes_cap = planes_bytes(max3<int64_t>(m, n, k));
+    p.e.ppart_elems = sliced_ppart_elems(max3<int64_t>(m, n, k));
+    p.e.planes = cv.take<char>(p.e.planes_cap);
+    // X is one of A (m x n), W (m x k), H (k x n) or a transpose of those
+    p.e.ppart = cv.take<float>(sliced_ppart_elems(max3<int64_t>(m, n, k)));
+    p.At = cv.take<float>((size_t)m * n);
+    p.Wt = cv.take<float>((size_t)k * m);
+    p.Ht = cv.take<float>((size_t)n * k);
+    p.num = cv.take<float>((size_t)k * big);
+    p.den = cv.take<float>((size_t)k * big);
+    p.gw = cv.take<float>((size_t)k * k);
+    p.gh = cv.take<float>((size_t)k * k);
+    if (bytes) *bytes = cv.off;
+    return p;
+}
+
+size_t sliced_dense_bytes(int64_t m, int64_t n, int k)
+{
+    size_t b = 0;
+    carve_sliced_dense(nullptr, m, n, k, &b);
+    return b;
+}
+
+int sliced_dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, int iters,
+                      float eps, const SlicedDense &p, hipStream_t st)
+{
+    NMF_HIP(launch_transpose(A, m, n, p.At, st));
+    NMF_HIP(launch_transpose(W, m, k, p.Wt, st));
+    for (int it = 0; it < iters; ++it) {
+        // H update (Algorithm 3 order): numerator W^T A, denominator (W^T W) H
+        if (int rc = sliced_ftx(p.e, W, m, k, A, n, p.num, false, st)) return rc;
+        if (int rc = sliced_ftx(p.e, W, m, k, W, k, p.gw, false, st)) return rc;
+        if (int rc = sliced_ftx(p.e, p.gw, k, k, H, n, p.den, false, st)) return rc;
+        NMF_HIP(launch_mu_apply(H, p.num, p.den, eps, (int64_t)k * n, st));
+        NMF_HIP(launch_transpose(H, k, n, p.Ht, st));
+        // W update with the new H, on the transposes: (A H^T)^T = H A^T, (W H H^T)^T = (H H^T) W^T
+        if (int rc = sliced_ftx(p.e, p.Ht, n, k, p.At, m, p.num, false, st)) return rc;
+        if (int rc = sliced_ftx(p.e, p.Ht, n, k, p.Ht, k, p.gh, false, st)) return rc;
+        if (int rc = sliced_ftx(p.e, p.gh, k, k, p.Wt, m, p.den, false, st)) return rc;
+        NMF_HIP(launch_mu_apply(p.Wt, p.num, p.den, eps, (int64_t)k * m, st));
+        NMF_HIP(launch_transpose(p.Wt, k, m, W, st));
+    }
+    return NMF_OK;
+}
+
+// Out-of-memory run through the sliced engine, any supported rank; W either on the device
+// (W_host == nullptr) or in host memory and streamed with the batches (Algorithm 5).
+constexpr int kMaxSlots = 16;
+
+struct SlicedOoc {
+    Sliced e;
+    float *Abt, *Wbt, *num_b, *den_b;   // per-batch transposes, numerator and denominator (k x rows)
+    float *num, *den, *Ht, *gw, *gh;    // k x n, k x n, n x k, k x k, k x k
+};
+
+SlicedOoc carve_sliced_ooc(void *ws, int64_t rb, int64_t n, int k, size_t *bytes)
+{
+    Carve cv(ws);
+    SlicedOoc p;
+    cv.take<unsigned>(64);
+    p.e.planes_cap = planes_bytes(max3<int64_t>(rb, n, k));
+    p.e.ppart_elems = sliced_ppart_elems(max3<int64_t>(rb, n, k));
+    p.e.planes = cv.take<char>(p.e.planes_cap);
+    p.e.ppart = cv.take<float>(sliced_ppart_elems(max3<int64_t>(rb, n, k)));
+    p.Abt = cv.take<float>((size_t)n * rb);
+    p.Wbt = cv.take<float>((size_t)k * rb);
+    p.num_b = cv.take<float>((size_t)k * rb);
+    p.den_b = cv.take<float>((size_t)k * rb);
+    p.num = cv.take<float>((size_t)k * n);
+    p.den = cv.take<float>((size_t)k * n);
+    p.Ht = cv.take<float>((size_t)n * k);
+    p.gw = cv.take<float>((size_t)k * k);
+    p.gh = cv.take<float>((size_t)k * k);
+    if (bytes) *bytes = cv.off;
+    return p;
+}
+
+size_t sliced_ooc_bytes(int64_t rb, int64_t n, int k)
+{
+    size_t b = 0;
+    carve_sliced_ooc(nullptr, rb, n, k, &b);
+    return b;
+}
+
+int sliced_ooc_run(const float *A_host, float *W_host, float *W_dev, int64_t m, int64_t n, int k,
+                   float *H, int iters, float eps, int64_t batch_rows, int slots, hipStream_t st,
+                   size_t *device_bytes)
+{
+    const bool hostw = W_host != nullptr;
+    const size_t a_bytes = align_up((size_t)batch_rows * n * sizeof(float));
+    const size_t w_bytes = hostw ? align_up((size_t)batch_rows * k * sizeof(float)) : 0;
+    const size_t slot_bytes = a_bytes + w_bytes;
+    void *ws = nullptr;
+    const size_t ws_bytes = sliced_ooc_bytes(batch_rows, n, k);
+    if (int rc = ensure_workspace(ws_bytes, &ws)) return rc;
+    const SlicedOoc p = carve_sliced_ooc(ws, batch_rows, n, k, nullptr);
+    if (g.sl_stage_bytes < slots * slot_bytes) {
+        if (g.sl_stage) {
+            NMF_HIP(hipDeviceSynchronize());
+            NMF_HIP(hipFree(g.sl_stage));
+            g.sl_stage = nullptr;
+            g.sl_stage_bytes = 0;
+        }
+        hipError_t e = hipMalloc(&g.sl_stage, slots * slot_bytes);
+        if (e != hipSuccess) return fail(NMF_ENOMEM, "hipMalloc(staging): %s", hipGetErrorString(e));
+        g.sl_stage_bytes = slots * slot_bytes;
+    }
+    if (device_bytes) *device_bytes = ws_bytes + slots * slot_bytes;
+    if (!g.copy_stream) NMF_HIP(hipStreamCreateWithFlags(&g.copy_stream, hipStreamNonBlocking));
+    if (!g.ev_entry) NMF_HIP(hipEventCreateWithFlags(&g.ev_entry, hipEventDisableTiming));
+    if (!g.back_stream) NMF_HIP(hipStreamCreateWithFlags(&g.back_stream, hipStreamNonBlocking));
+    for (int i = 0; i < kMaxSlots; ++i) {
+        if (!g.sl_copied[i]) NMF_HIP(hipEventCreateWithFlags(&g.sl_copied[i], hipEventDisableTiming));
+        if (!g.sl_done[i]) NMF_HIP(hipEventCreateWithFlags(&g.sl_done[i], hipEventDisableTiming));
+        if (!g.sl_freed[i]) NMF_HIP(hipEventCreateWithFlags(&g.sl_freed[i], hipEventDisableTiming));
+    }
+    // Staging slots may still be read by work enqueued earlier on `st`.
+    NMF_HIP(hipEventRecord(g.ev_entry, st));
+    NMF_HIP(hipStreamWaitEvent(g.copy_stream, g.ev_entry, 0));
+
+    const int64_t nb = (m + batch_rows - 1) / batch_rows;
+    int64_t issued = 0;
+    for (int s = 0; s <= iters; ++s) {
+        for (int64_t b = 0; b < nb; ++b, ++issued) {
+            const int slot = (int)(issued % slots);
+            const int64_t i0 = b * batch_rows;
+            const int64_t rb = (i0 + batch_rows <= m) ? batch_rows : m - i0;
+            char *base = static_cast<char *>(g.sl_stage) + slot * slot_bytes;
+            float *Ab = reinterpret_cast<float *>(base);
+            float *Wb = hostw ? reinterpret_cast<float *>(base + a_bytes) : W_dev + i0 * k;
+            if (issued >= slots) NMF_HIP(hipStreamWaitEvent(g.copy_stream, g.sl_freed[slot], 0));
+            NMF_HIP(hipMemcpyAsync(Ab, A_host + i0 * n, (size_t)rb * n * sizeof(float),
+                                   hipMemcpyHostToDevice, g.copy_stream));
+            if (hostw)
+                NMF_HIP(hipMemcpyAsync(Wb, W_host + i0 * k, (size_t)rb * k * sizeof(float),
+                                       hipMemcpyHostToDevice, g.copy_stream));
+            NMF_HIP(hipEventRecord(g.sl_copied[slot], g.copy_stream));
+            NMF_HIP(hipStreamWaitEvent(st, g.sl_copied[slot], 0));
+            if (s > 0) {
+                // W_b <- W_b * (A_b H^T) / (W_b H H^T + eps) on the transposes of the batch
+                NMF_HIP(launch_transpose(Ab, rb, n, p.Abt, st));
+                NMF_HIP(launch_transpose(Wb, rb, k, p.Wbt, st));
+                if (int rc = sliced_ftx(p.e, p.Ht, n, k, p.Abt, rb, p.num_b, false, st)) return rc;
+                if (int rc = sliced_ftx(p.e, p.gh, k, k, p.Wbt, rb, p.den_b, false, st)) return rc;
+                NMF_HIP(launch_mu_apply(p.Wbt, p.num_b, p.den_b, eps, (int64_t)k * rb, st));
+                NMF_HIP(launch_transpose(p.Wbt, k, rb, Wb, st));
+            }
+            if (s < iters) {
+                // accumulate W_b^T A_b and W_b^T W_b with the W_b just updated
+                if (int rc = sliced_ftx(p.e, Wb, rb, k, Ab, n, p.num, b > 0, st)) return rc;
+                if (int rc = sliced_ftx(p.e, Wb, rb, k, Wb, k, p.gw, b > 0, st)) return rc;
+            }
+            if (hostw) {
+                NMF_HIP(hipEventRecord(g.sl_done[slot], st));
+                NMF_HIP(hipStreamWaitEvent(g.back_stream, g.sl_done[slot], 0));
+                if (s > 0)
+                    NMF_HIP(hipMemcpyAsync(W_host + i0 * k, Wb, (size_t)rb * k * sizeof(float),
+                                           hipMemcpyDeviceToHost, g.back_stream));
+                NMF_HIP(hipEventRecord(g.sl_freed[slot], g.back_stream));
+            } else {
+                NMF_HIP(hipEventRecord(g.sl_freed[slot], st));
+            }
+        }
+        if (s < iters) {
+            if (int rc = sliced_ftx(p.e, p.gw, k, k, H, n, p.den, false, st)) return rc;
+            NMF_HIP(launch_mu_apply(H, p.num, p.den, eps, (int64_t)k * n, st));
+            NMF_HIP(launch_transpose(H, k, n, p.Ht, st));
+            if (int rc = sliced_ftx(p.e, p.Ht, n, k, p.Ht, k, p.gh, false, st)) return rc;
+        }
+    }
+    if (hostw) {
+        // the caller's stream continues only after the last rows of W have reached the host
+        NMF_HIP(hipEventRecord(g.ev_entry, g.back_stream));
+        NMF_HIP(hipStreamWaitEvent(st, g.ev_entry, 0));
+    }
+    return NMF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -308,7 +543,13 @@ const char *nmf_last_error(void) { return t_err; }
 size_t nmf_mu_workspace_bytes(int kind, int64_t m, int64_t n, int64_t nnz, int32_t k,
                               int64_t batch_rows)
 {
-    if (m < 1 || n < 1 || k < 1 || k > NMF_MU_MAX_K) return 0;
+    if (m < 1 || n < 1 || k < 1) return 0;
+    if (kind == 5) return k > NMF_MU_MAX_K_SLICED ? 0 : sliced_dense_bytes(m, n, k);
+    if (kind == 6) {
+        if (batch_rows < 1 || k > NMF_MU_MAX_K_SLICED) return 0;
+        return sliced_ooc_bytes(batch_rows < m ? batch_rows : m, n, k);
+    }
+    if (k > NMF_MU_MAX_K) return 0;
     switch (kind) {
     case 0: return dense_bytes(m, n, k, true);
     case 3:   // stacks of runs up to the largest supported rank, plus their packed factors
@@ -359,6 +600,9 @@ int nmf_mu_release(void)
     if (g.stage) NMF_HIP(hipFree(g.stage));
     g.stage = nullptr;
     g.stage_bytes = 0;
+    if (g.sl_stage) NMF_HIP(hipFree(g.sl_stage));
+    g.sl_stage = nullptr;
+    g.sl_stage_bytes = 0;
     for (int i = 0; i < 3; ++i) {
         if (g.ev_copied[i]) NMF_HIP(hipEventDestroy(g.ev_copied[i]));
         if (g.ev_freed[i]) NMF_HIP(hipEventDestroy(g.ev_freed[i]));
@@ -368,16 +612,29 @@ int nmf_mu_release(void)
     g.ev_entry = nullptr;
     if (g.copy_stream) NMF_HIP(hipStreamDestroy(g.copy_stream));
     g.copy_stream = nullptr;
+    for (int i = 0; i < 16; ++i) {
+        if (g.sl_copied[i]) NMF_HIP(hipEventDestroy(g.sl_copied[i]));
+        if (g.sl_done[i]) NMF_HIP(hipEventDestroy(g.sl_done[i]));
+        if (g.sl_freed[i]) NMF_HIP(hipEventDestroy(g.sl_freed[i]));
+        g.sl_copied[i] = g.sl_done[i] = g.sl_freed[i] = nullptr;
+    }
+    if (g.back_stream) NMF_HIP(hipStreamDestroy(g.back_stream));
+    g.back_stream = nullptr;
     return NMF_OK;
 }
 
 int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
                  int32_t iters, float eps, void *stream)
 {
-    if (int rc = check_common(A, W, H, m, n, k, iters, eps)) return rc;
+    if (int rc = check_common(A, W, H, m, n, k, iters, eps, NMF_MU_MAX_K_SLICED)) return rc;
     if (iters == 0) return NMF_OK;
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
+    if (k > NMF_MU_MAX_K) {
+        if (int rc = ensure_workspace(sliced_dense_bytes(m, n, k), &ws)) return rc;
+        const SlicedDense p = carve_sliced_dense(ws, m, n, k, nullptr);
+        return sliced_dense_body(A, m, n, k, W, H, iters, eps, p, static_cast<hipStream_t>(stream));
+    }
     bool mirrored = false;
     if (int rc = dense_workspace(m, n, k, &ws, &mirrored)) return rc;
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
@@ -540,7 +797,7 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
                int32_t iters, float eps, int64_t batch_rows, int64_t device_budget_bytes,
                void *stream)
 {
-    if (int rc = check_common(A_host, W, H, m, n, k, iters, eps)) return rc;
+    if (int rc = check_common(A_host, W, H, m, n, k, iters, eps, NMF_MU_MAX_K_SLICED)) return rc;
     if (batch_rows < 1) return fail(NMF_EINVAL, "batch_rows must be >= 1%s");
     if (device_budget_bytes < 1) return fail(NMF_EINVAL, "device_budget_bytes must be >= 1%s");
     if (iters == 0) return NMF_OK;
@@ -552,6 +809,11 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     std::lock_guard<std::mutex> lock(g.mu);
+    if (k > NMF_MU_MAX_K) {
+        const int64_t nbat = (m + batch_rows - 1) / batch_rows;
+        if (slots > nbat) slots = (int)nbat;
+        return sliced_ooc_run(A_host, nullptr, W, m, n, k, H, iters, eps, batch_rows, slots, st, nullptr);
+    }
     void *ws = nullptr;
     if (int rc = ensure_workspace(dense_bytes(batch_rows, n, k, false), &ws)) return rc;
     Carve cv(ws);
@@ -572,13 +834,11 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
         if (e != hipSuccess) return fail(NMF_ENOMEM, "hipMalloc(staging): %s", hipGetErrorString(e));
         g.stage_bytes = slots * slot_bytes;
     }
-    if (!g.copy_stream) {
-        NMF_HIP(hipStreamCreateWithFlags(&g.copy_stream, hipStreamNonBlocking));
-        for (int i = 0; i < 3; ++i) {
-            NMF_HIP(hipEventCreateWithFlags(&g.ev_copied[i], hipEventDisableTiming));
-            NMF_HIP(hipEventCreateWithFlags(&g.ev_freed[i], hipEventDisableTiming));
-        }
-        NMF_HIP(hipEventCreateWithFlags(&g.ev_entry, hipEventDisableTiming));
+    if (!g.copy_stream) NMF_HIP(hipStreamCreateWithFlags(&g.copy_stream, hipStreamNonBlocking));
+    if (!g.ev_entry) NMF_HIP(hipEventCreateWithFlags(&g.ev_entry, hipEventDisableTiming));
+    for (int i = 0; i < 3; ++i) {
+        if (!g.ev_copied[i]) NMF_HIP(hipEventCreateWithFlags(&g.ev_copied[i], hipEventDisableTiming));
+        if (!g.ev_freed[i]) NMF_HIP(hipEventCreateWithFlags(&g.ev_freed[i], hipEventDisableTiming));
     }
     // Staging slots may still be read by work enqueued earlier on `st`.
     NMF_HIP(hipEventRecord(g.ev_entry, st));
@@ -609,6 +869,23 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
         }
     }
     return NMF_OK;
+}
+
+int nmf_mu_ooc_hostw(const float *A_host, float *W_host, int64_t m, int64_t n, int32_t k, float *H,
+                     int32_t iters, float eps, int64_t batch_rows, int32_t slots, void *stream,
+                     size_t *device_bytes_host)
+{
+    if (int rc = check_common(A_host, W_host, H, m, n, k, iters, eps, NMF_MU_MAX_K_SLICED)) return rc;
+    if (batch_rows < 1) return fail(NMF_EINVAL, "batch_rows must be >= 1%s");
+    if (slots < 1 || slots > kMaxSlots) return fail(NMF_EINVAL, "slots must be in 1 .. 16%s");
+    if (device_bytes_host) *device_bytes_host = 0;
+    if (iters == 0) return NMF_OK;
+    if (batch_rows > m) batch_rows = m;
+    const int64_t nbat = (m + batch_rows - 1) / batch_rows;
+    if (slots > nbat) slots = (int)nbat;
+    std::lock_guard<std::mutex> lock(g.mu);
+    return sliced_ooc_run(A_host, W_host, nullptr, m, n, k, H, iters, eps, batch_rows, slots,
+                          static_cast<hipStream_t>(stream), device_bytes_host);
 }
 
 int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,

@@ -311,12 +311,14 @@ __global__ __launch_bounds__(64 * kWtaWaves, OCC) void wta_pass_kernel(const flo
 }
 
 // ---------------------------------------------------------------------------
-// Piece planes of a factor X (rows x k, row-major), the A_op of the pass below:
+// Piece planes of kc <= 32 columns c0 .. c0 + kc - 1 of a factor X (rows x ld,
+// row-major), the A_op of the pass below:
 // planes[(g * 3 + p) * 32 + c] = the eight bf16 p-th pieces (p = 0: h, 1: m, 2: l)
-// of X[8 g .. 8 g + 7][c], c < 32; rows beyond `rows` and factors beyond k are zero.
+// of X[8 g .. 8 g + 7][c0 + c], c < 32; rows beyond `rows` and columns beyond kc are zero.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restrict__ X, int64_t rows,
-                                                           int k, u32x4 *__restrict__ planes)
+                                                           int64_t ld, int64_t c0, int k,
+                                                           u32x4 *__restrict__ planes)
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t g = t >> 5;
@@ -329,7 +331,7 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
             const int64_t row = g * 8 + 2 * pr + e;
-            const float x = (row < rows && c < k) ? X[row * k + c] : 0.f;
+            const float x = (row < rows && c < k) ? X[row * ld + c0 + c] : 0.f;
             split3(x, h[e], m[e], l[e]);
         }
         o[0][pr] = pack2(h[0], h[1]);
@@ -874,13 +876,23 @@ __global__ void residual_finish_kernel(const double *__restrict__ partial, int64
 // P = sum over the row splits of the partial W^T A results (test entry point only).
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float *__restrict__ ppart,
                                                            int splits, int64_t count,
-                                                           float *__restrict__ P)
+                                                           float *__restrict__ P, int accumulate)
 {
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256) {
         float s = 0.f;
         for (int t = 0; t < splits; ++t) s += ppart[(int64_t)t * count + e];
-        P[e] = s;
+        P[e] = accumulate ? P[e] + s : s;
     }
+}
+
+// X <- X * P / (D + eps) element by element: the multiplicative update with its numerator P
+// and the product D of the other factor's Gram matrix with X already formed (ranks above 64).
+__global__ __launch_bounds__(256) void mu_apply_kernel(float *__restrict__ X, const float *__restrict__ P,
+                                                       const float *__restrict__ D, float eps,
+                                                       int64_t count)
+{
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256)
+        X[e] = X[e] * P[e] / (D[e] + eps);
 }
 
 // ---------------------------------------------------------------------------
@@ -957,12 +969,28 @@ static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, co
 
 size_t planes_bytes(int64_t rows) { return (size_t)((rows + 7) / 8) * 3 * 32 * 16; }
 
+hipError_t launch_split_planes_slice(const float *X, int64_t rows, int64_t ld, int64_t c0, int kc,
+                                     void *planes, hipStream_t st)
+{
+    if (kc < 1 || kc > 32) return hipErrorInvalidValue;
+    const int64_t threads = ((rows + 7) / 8) * 32;
+    hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, X,
+                       rows, ld, c0, kc, static_cast<u32x4 *>(planes));
+    return hipGetLastError();
+}
+
 hipError_t launch_split_planes(const float *X, int64_t rows, int k, void *planes, hipStream_t st)
 {
     if (!wta_uses_planes(k)) return hipSuccess;
-    const int64_t threads = ((rows + 7) / 8) * 32;
-    hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, X,
-                       rows, k, static_cast<u32x4 *>(planes));
+    return launch_split_planes_slice(X, rows, k, 0, k, planes, st);
+}
+
+hipError_t launch_mu_apply(float *X, const float *P, const float *D, float eps, int64_t count,
+                           hipStream_t st)
+{
+    int64_t b = (count + 255) / 256;
+    if (b > 8192) b = 8192;
+    hipLaunchKernelGGL(mu_apply_kernel, dim3((unsigned)b), dim3(256), 0, st, X, P, D, eps, count);
     return hipGetLastError();
 }
 
@@ -1035,11 +1063,11 @@ hipError_t launch_factor_update(float *X, float *Xt, const float *part, int spli
 }
 
 hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
-                               hipStream_t st)
+                               hipStream_t st, bool accumulate)
 {
     int64_t b = (count + 255) / 256;
     if (b > 4096) b = 4096;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b), dim3(256), 0, st, ppart, splits, count, P);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b), dim3(256), 0, st, ppart, splits, count, P, accumulate ? 1 : 0);
     return hipGetLastError();
 }
 

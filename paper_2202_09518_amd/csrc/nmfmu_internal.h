@@ -44,15 +44,21 @@ hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *g
 inline bool wta_uses_planes(int k) { return k <= 32; }
 size_t planes_bytes(int64_t rows);
 hipError_t launch_split_planes(const float *X, int64_t rows, int k, void *planes, hipStream_t st);
+// The same for columns c0 .. c0 + kc - 1 (kc <= 32) of X with leading dimension ld.
+hipError_t launch_split_planes_slice(const float *X, int64_t rows, int64_t ld, int64_t c0, int kc,
+                                     void *planes, hipStream_t st);
 // ppart[s] (+)= W[r0_s:r1_s]^T A[r0_s:r1_s] for each row split s (k x n each).  `planes`:
 // scratch of planes_bytes(rows) bytes (unused unless wta_uses_planes(k)); with planes_ready it
 // already holds the planes of W, otherwise they are produced first.
 hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
                            void *planes, bool planes_ready, float *ppart, int splits,
                            int64_t rows_per_split, bool accumulate, hipStream_t st);
-// P[e] = sum_s ppart[s][e], e < count.
+// P[e] (+)= sum_s ppart[s][e], e < count.
 hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
-                               hipStream_t st);
+                               hipStream_t st, bool accumulate = false);
+// X[e] <- X[e] * P[e] / (D[e] + eps), e < count.
+hipError_t launch_mu_apply(float *X, const float *P, const float *D, float eps, int64_t count,
+                           hipStream_t st);
 // X (k x len) <- X * (sum_s part[s]) / (G X + eps), in place.  G is given complete (Gfull, ld k)
 // or as nbin partial tiles (gin).  Optional: Xt (len x k) = new X^T; gout = partial Gram tiles
 // of the new X, one set per block (factor_update_blocks(len) blocks); planes = the bf16 piece

@@ -64,6 +64,12 @@ def test_workspace_bytes():
     assert d + extra <= wb(0, 32768, 16384, 0, 32, 0) <= d + extra + (1 << 20)
     assert wb(1, 1000, 5000, 123, 8, 0) >= 2 * 5000 * 8 * 4
     assert wb(2, 262144, 65536, 0, 64, 8192) == wb(4, 8192, 65536, 0, 64, 0)
+    # rank-sliced plans: A^T, W^T, H^T and two k x max(m, n) arrays at least / the batch versions
+    assert wb(5, 1000, 600, 0, 1025, 0) == 0
+    assert wb(5, 1000, 600, 0, 100, 0) >= (1000 * 600 + 2 * 100 * 1000 + 100 * 1000 + 600 * 100) * 4
+    assert wb(6, 1000, 600, 0, 100, 0) == 0     # needs batch_rows
+    assert wb(6, 1000, 600, 0, 100, 128) >= (600 * 128 + 3 * 100 * 128 + 2 * 100 * 600) * 4
+    assert wb(6, 1000, 600, 0, 100, 128) < wb(5, 1000, 600, 0, 100, 0)
 
 
 def test_argument_errors_need_no_device():
@@ -74,7 +80,12 @@ def test_argument_errors_need_no_device():
     assert L.nmf_mu_dense(null, 4, 4, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_dense(one, 0, 4, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_dense(one, 4, 4, 0, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
-    assert L.nmf_mu_dense(one, 4, 4, 65, one, one, 1, 1e-16, null) == nmf.NMF_EUNSUPPORTED
+    assert L.nmf_mu_dense(one, 4, 4, 1025, one, one, 1, 1e-16, null) == nmf.NMF_EUNSUPPORTED
+    assert L.nmf_mu_csr(one, one, one, 4, 4, 3, 65, one, one, 1, 1e-16, null) == nmf.NMF_EUNSUPPORTED
+    assert L.nmf_mu_ooc_hostw(one, one, 4, 4, 2, one, 1, 1e-16, 2, 0, null, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_ooc_hostw(one, one, 4, 4, 2, one, 1, 1e-16, 2, 17, null, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_ooc_hostw(one, null, 4, 4, 2, one, 1, 1e-16, 2, 2, null, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_ooc_hostw(one, one, 4, 4, 2, one, 0, 1e-16, 2, 2, null, null) == nmf.NMF_OK
     assert L.nmf_mu_dense(one, 4, 4, 2, one, one, -1, 1e-16, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_dense(one, 4, 4, 2, one, one, 1, -1.0, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_dense(one, 4, 4, 2, one, one, 1, float("nan"), null) == nmf.NMF_EINVAL

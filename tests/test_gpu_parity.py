@@ -344,6 +344,88 @@ def test_ooc_pageable_host_memory_and_config1():
     check(host(Wd), host(Hd), Wr, Hr, TOLN)
 
 
+# ---- ranks above 64 (rank-sliced engine) and the host-resident-W pipeline ---------------
+
+@pytest.mark.parametrize("m,n,k,iters", [(300, 200, 65, 1), (515, 260, 100, 1), (257, 1031, 96, 2),
+                                         (130, 70, 130, 1), (1000, 520, 70, 5)])
+def test_mu_dense_ranks_above_64(m, n, k, iters):
+    A, W, H = case(m, n, k, 70)
+    Wg, Hg = run_dense(A, W, H, iters)
+    Wr, Hr = orc.mu_dense(A, W, H, iters, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, TOL1 if iters == 1 else 1e-4)
+
+
+def test_mu_dense_rank_256_planted():
+    """A larger rank on planted data, several iterations, and determinism."""
+    m, n, k = 1536, 1024, 256
+    A = nmf_inputs.dense_planted(m, n, 64, seed=1010).numpy()
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=2010))
+    Wg, Hg = run_dense(A, W, H, 3)
+    Wr, Hr = orc.mu_dense(A, W, H, 3, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 1e-4)
+    Wg2, Hg2 = run_dense(A, W, H, 3)
+    np.testing.assert_array_equal(Wg, Wg2)
+    np.testing.assert_array_equal(Hg, Hg2)
+
+
+def run_hostw(A, W, H, iters, batch_rows, slots, pinned=True):
+    m, n = A.shape
+    k = W.shape[1]
+    Ah, Wh = torch.from_numpy(np.ascontiguousarray(A)), torch.from_numpy(np.ascontiguousarray(W)).clone()
+    if pinned:
+        Ah, Wh = Ah.pin_memory(), Wh.pin_memory()
+    Hd = dev(H)
+    used = nmf.nmf_mu_ooc_hostw(Ah, Wh, m, n, k, Hd, iters, EPS, batch_rows, slots)
+    torch.cuda.synchronize()
+    return Wh.numpy().astype(np.float64), host(Hd), used
+
+
+@pytest.mark.parametrize("m,n,k,batch,slots,iters", [
+    (256, 192, 4, 48, 3, 3), (300, 200, 40, 64, 1, 2), (300, 200, 40, 64, 2, 2), (300, 200, 40, 301, 4, 2),
+    (515, 260, 100, 100, 16, 2), (257, 131, 17, 1, 3, 1), (130, 1027, 33, 50, 2, 1)])
+def test_ooc_hostw_matches_oracle(m, n, k, batch, slots, iters):
+    A, W, H = case(m, n, k, 80)
+    Wg, Hg, used = run_hostw(A, W, H, iters, batch, slots)
+    Wr, Hr = orc.mu_dense(A, W, H, iters, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, TOL1 if iters == 1 else 1e-4)
+    nb = -(-m // min(batch, m))
+    rows = min(batch, m)
+    # staging: min(slots, batches) slots of a batch of A and of W; the rest is the workspace
+    ws = nmf.nmf_mu_workspace_bytes(6, m, n, 0, k, batch)
+    assert used >= ws + min(slots, nb) * rows * (n + k) * 4
+    assert used <= ws + min(slots, nb) * (rows * (n + k) * 4 + 512)
+
+
+def test_ooc_hostw_config1_100_iterations_pageable_memory():
+    A, W, H = config1()
+    Wg, Hg, _ = run_hostw(A, W, H, 100, 48, 3, pinned=False)
+    Wr, Hr = orc.mu_dense(A, W, H, 100, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, TOLN)
+
+
+def test_ooc_hostw_slot_count_does_not_change_the_result():
+    A, W, H = case(700, 300, 48, 81)
+    ref = run_hostw(A, W, H, 3, 96, 1)
+    for slots in (2, 5, 16):
+        got = run_hostw(A, W, H, 3, 96, slots)
+        np.testing.assert_array_equal(ref[0], got[0])
+        np.testing.assert_array_equal(ref[1], got[1])
+        assert got[2] > ref[2] or slots > 8
+
+
+def test_ooc_device_w_rank_above_64():
+    A, W, H = case(515, 260, 100, 82)
+    Wd, Hd = dev(W), dev(H)
+    Ah = torch.from_numpy(A).pin_memory()
+    nmf.nmf_mu_ooc(Ah, 515, 260, 100, Wd, Hd, 2, EPS, 128, 3 * 128 * 260 * 4 + 4096)
+    Wr, Hr = orc.mu_dense(A, W, H, 2, float(np.float32(EPS)))
+    check(host(Wd), host(Hd), Wr, Hr, 1e-4)
+    # same engine, same batches: the host-W pipeline gives the same bits
+    Wg, Hg, _ = run_hostw(A, W, H, 2, 128, 3)
+    np.testing.assert_array_equal(host(Wd), Wg)
+    np.testing.assert_array_equal(host(Hd), Hg)
+
+
 # ---- CSR path --------------------------------------------------------------------
 
 def run_csr(rowptr, colidx, vals, m, n, W, H, iters):
