@@ -191,6 +191,81 @@ def bench_c4(args, torch, nmf, nmf_inputs):
             "h2d_gbs_achieved": gbs, "h2d_gbs_bare_copy": copy_gbs, "frac_of_bare_copy": gbs / copy_gbs}
 
 
+def bench_oom1(args, torch, nmf, nmf_inputs):
+    """The paper's own out-of-memory benchmark shape (section 4.4): 524288 x 4096 fp32 (8 GiB) in 32
+    row batches, A and W in pinned host memory, W_b up and down per batch (Algorithm 5), a sweep
+    over the number of staging slots standing in for the stream-queue size q_s."""
+    m, n, k, nbatch = 524288, 4096, args.k, 32
+    if args.small:
+        m //= 8
+    batch = m // nbatch
+    Ah = torch.empty((m, n), dtype=torch.float32, pin_memory=True)
+    nmf_inputs.dense_planted(m, n, 32, seed=1006, device="cuda", out=Ah, row_block=batch)
+    W0, H0 = nmf_inputs.init_factors(m, n, k, seed=2006, device="cuda")
+    Wh = torch.empty((m, k), dtype=torch.float32, pin_memory=True)
+    torch.cuda.synchronize()
+    # bare copy ceiling of what one sweep moves up: A_b and W_b per batch, one stream
+    sa = torch.empty((batch, n), dtype=torch.float32, device="cuda")
+    sw = torch.empty((batch, k), dtype=torch.float32, device="cuda")
+    Wh.copy_(W0)
+    torch.cuda.synchronize()
+    sa.copy_(Ah[:batch], non_blocking=True)
+    t0 = sync_time(torch)
+    for b in range(nbatch):
+        sa.copy_(Ah[b * batch:(b + 1) * batch], non_blocking=True)
+        sw.copy_(Wh[b * batch:(b + 1) * batch], non_blocking=True)
+    t1 = sync_time(torch)
+    up_bytes = m * (n + k) * 4
+    copy_gbs = up_bytes / (t1 - t0) / 1e9
+    del sa, sw
+    log(f"[bench] oom1: {m}x{n}, k={k}, {nbatch} batches of {batch} rows; bare pinned H2D copy {copy_gbs:.1f} GB/s")
+    iters = args.steps
+    sweep = []
+    for slots in [int(x) for x in args.slots.split(",")]:
+        Wh.copy_(W0)
+        H = H0.clone()
+        torch.cuda.synchronize()
+        t0 = sync_time(torch)
+        used = nmf.nmf_mu_ooc_hostw(Ah, Wh, m, n, k, H, iters, EPS, batch, slots)
+        t1 = sync_time(torch)
+        assert bool(torch.isfinite(H).all()) and bool(torch.isfinite(Wh).all())
+        model = min(slots, nbatch) * batch * (n + k) * 4          # the O(p n q_s) term: staged batches
+        sweep.append({"slots": slots, "ms_per_iteration": (t1 - t0) * 1e3 / iters,
+                      "h2d_gbs": (iters + 1) * up_bytes / (t1 - t0) / 1e9,
+                      "device_bytes": used, "staged_batches_bytes": model})
+        log(f"[bench] oom1: slots={slots}: {sweep[-1]}")
+    best = min(sweep, key=lambda x: x["ms_per_iteration"])
+    return {"metric": "MU iterations/s (dense fp32, A and W streamed from pinned host memory)",
+            "value": 1e3 / best["ms_per_iteration"], "unit": "iterations/s", "n_gpus": 1, "steps": iters, "warmup": 0,
+            "ms_per_step": best["ms_per_iteration"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"oom1: dense {m}x{n} and W {m}x{k} in pinned host memory, {nbatch} batches, "
+                                   f"{iters} iterations = {iters + 1} sweeps, best of slots={args.slots}"},
+            "h2d_gbs_achieved": best["h2d_gbs"], "h2d_gbs_bare_copy": copy_gbs,
+            "frac_of_bare_copy": best["h2d_gbs"] / copy_gbs, "slot_sweep": sweep}
+
+
+def bench_ck(args, torch, nmf, nmf_inputs):
+    """Resident dense run at a rank above 64 (rank-sliced engine) on config 2's matrix."""
+    m, n, k = 32768, 16384, args.k
+    A = nmf_inputs.dense_planted(m, n, 32, seed=1002, device="cuda")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2002, device="cuda")
+    nmf.nmf_mu_dense(A, m, n, k, W, H, max(args.warmup, 1), EPS)
+    t0 = sync_time(torch)
+    nmf.nmf_mu_dense(A, m, n, k, W, H, args.steps, EPS)
+    t1 = sync_time(torch)
+    ms_step = (t1 - t0) * 1e3 / args.steps
+    assert bool(torch.isfinite(W).all()) and bool(torch.isfinite(H).all())
+    slices = (k + 31) // 32
+    flop = 4.0 * m * n * k + 4.0 * k * k * (m + n)
+    return {"metric": "MU iterations/s (dense fp32, resident A, rank-sliced)", "value": 1e3 / ms_step,
+            "unit": "iterations/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+            "config": {"workload": f"ck: dense {m}x{n} resident, k={k} ({slices} slices of 32 factors)"},
+            "gbs_over_A_reads": 2 * slices * m * n * 4 / (ms_step * 1e-3) / 1e9,
+            "tflops_useful": flop / (ms_step * 1e-3) / 1e12}
+
+
 def bench_c5(args, torch, nmf, nmf_inputs):
     m, n = 16384, 8192
     kmin, kmax, copies = args.kmin, args.kmax, args.copies
@@ -220,7 +295,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5", "oom1", "ck"])
+    ap.add_argument("--k", type=int, default=128, help="rank of the oom1 / ck workloads")
+    ap.add_argument("--slots", default="1,2,3,4,8", help="staging slot counts swept by oom1")
     ap.add_argument("--small", action="store_true", help="reduced c3/c4 sizes (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate", action="store_true", help="also run one plain device copy of A (counter scaling)")
@@ -239,7 +316,8 @@ def main():
         sys.exit(2)
     nmf.lib()   # fail loudly if the HIP library is missing
     torch.cuda.set_device(0)
-    fn = {"c1": bench_c1, "c2": bench_c2, "c3": bench_c3, "c4": bench_c4, "c5": bench_c5}[args.workload]
+    fn = {"c1": bench_c1, "c2": bench_c2, "c3": bench_c3, "c4": bench_c4, "c5": bench_c5, "oom1": bench_oom1,
+          "ck": bench_ck}[args.workload]
     out = fn(args, torch, nmf, nmf_inputs)
     print(json.dumps(out), flush=True)
 

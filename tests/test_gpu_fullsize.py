@@ -106,3 +106,38 @@ def test_config5_shape_one_copy_1_and_100_iterations(k):
         ew, eh = errs(Wd, Hd, Wr, Hr)
         say(f"config 5 shape, k={k}, {iters} iterations: rel err W {ew:.2e} H {eh:.2e}")
         assert max(ew, eh) < (1e-5 if iters == 1 else 1e-3)
+
+
+def test_oom1_shape_host_resident_w_rank_128_two_iterations():
+    """The paper's out-of-memory benchmark shape (section 4.4): 524288 x 4096 in 32 batches, A and W
+    in pinned host memory, through the entry point and slot count bench.py --workload oom1 times."""
+    m, n, k, nbatch = 524288, 4096, 128, 32
+    batch = m // nbatch
+    Ah = torch.empty((m, n), dtype=torch.float32, pin_memory=True)
+    nmf_inputs.dense_planted(m, n, 32, seed=1006, device="cuda", out=Ah, row_block=batch)
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2006, device="cuda")
+    W0, H0 = W.cpu().numpy(), H.cpu().numpy()
+    Wh = torch.empty((m, k), dtype=torch.float32, pin_memory=True)
+    Wh.copy_(W)
+    del W
+    torch.cuda.synchronize()
+    nmf.nmf_mu_ooc_hostw(Ah, Wh, m, n, k, H, 2, EPS, batch, 3)
+    torch.cuda.synchronize()
+    say("oom1 shape: running the oracle (2 iterations, k = 128)")
+    Wr, Hr = orc.mu_dense(Ah.numpy(), W0, H0, 2, EPSD)
+    ew, eh = orc.rel_fro(Wh.numpy(), Wr), orc.rel_fro(H.cpu().numpy(), Hr)
+    say(f"oom1 shape, host-resident W, k = 128, 2 iterations: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 2e-5
+
+
+def test_rank_1024_resident_one_iteration():
+    """The largest supported rank on a matrix the oracle finishes in well under a minute."""
+    m, n, k = 16384, 4096, 1024
+    A = nmf_inputs.dense_planted(m, n, 32, seed=1007, device="cuda")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2007, device="cuda")
+    Ah, W0, H0 = A.cpu().numpy(), W.cpu().numpy(), H.cpu().numpy()
+    nmf.nmf_mu_dense(A, m, n, k, W, H, 1, EPS)
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 1, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    say(f"rank 1024 resident, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 1e-5
