@@ -188,6 +188,27 @@ int nmf_mu_ooc_hostw(const float *A_host, float *W_host, int64_t m, int64_t n, i
                      void *stream, size_t *device_bytes_host);
 
 /*
+ * Out-of-memory CSR MU (sections 2.3 and 3.2 together: the sparse matrix does
+ * not fit the device): the CSR arrays stay in host memory (pinned for overlap)
+ * and are streamed every sweep in batches of whole rows holding about
+ * `batch_nnz` stored entries each (a longer single row is a batch by itself);
+ * W, H and the k x k matrices stay on the device.  Sweep order and result as
+ * nmf_mu_ooc / nmf_mu_csr.  Per batch: W update of its rows by the row gather;
+ * a column-ordered copy of the batch (device sort) and the column gather, which
+ * adds the batch's share of W^T A to an n x k numerator; after the sweep the H
+ * update from that numerator.  k <= NMF_MU_MAX_K, m < 2^31, a batch < 2^31 entries.
+ *   device_budget_bytes  bound on the staging memory: min(3, what fits) slots
+ *                        of one batch (12 bytes per entry + 8 per row)
+ * The workspace (about 40 bytes per entry of the largest batch + 8 n k bytes)
+ * is sized inside the call; a caller-provided workspace must be large enough.
+ * Reads rowptr_host on the calling thread to form the batches.
+ */
+int nmf_mu_csr_ooc(const int64_t *rowptr_host, const int32_t *colidx_host, const float *vals_host,
+                   int64_t m, int64_t n, int64_t nnz, int32_t k, float *W, float *H,
+                   int32_t iters, float eps, int64_t batch_nnz, int64_t device_budget_bytes,
+                   void *stream);
+
+/*
  * Ensemble of independent resident dense runs of one shape (the perturbed
  * copies times rank sweep that model selection needs, sections 1 and 4.5).
  * Run r factorises A[r] (m x n) with rank k[r] into W[r] (m x k[r]) and H[r]

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_csr_partition", "nmf_split_planes", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_mu_dense_tol.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
     L.nmf_mu_csr.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp]
     L.nmf_mu_ooc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
+    L.nmf_mu_csr_ooc.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
     L.nmf_mu_ooc_hostw.argtypes = [vp, vp, i64, i64, i32, vp, i32, f32, i64, i32, vp, vp]
     L.nmf_mu_dense_batched.argtypes = [i32, vp, i64, i64, vp, vp, vp, i32, f32, vp]
     L.nmf_mu_workspace_bytes.restype = ctypes.c_size_t
@@ -161,6 +162,17 @@ def nmf_mu_ooc_hostw(A_host, W_host, m, n, k, H, iters, eps, batch_rows, slots, 
     _check(lib().nmf_mu_ooc_hostw(A_host.data_ptr(), W_host.data_ptr(), m, n, k, _dev(H, torch.float32, "H"),
                                   iters, eps, batch_rows, slots, _stream(stream), ctypes.byref(used)))
     return int(used.value)
+
+
+def nmf_mu_csr_ooc(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, batch_nnz, device_budget_bytes,
+                   stream=None) -> None:
+    """rowptr (int64), colidx (int32), vals (float32): contiguous HOST tensors (pinned for overlap)."""
+    for t, dt, what in ((rowptr, torch.int64, "rowptr"), (colidx, torch.int32, "colidx"), (vals, torch.float32, "vals")):
+        if t.is_cuda or t.dtype != dt or not t.is_contiguous():
+            raise ValueError(f"{what}: need a contiguous {dt} host tensor")
+    _check(lib().nmf_mu_csr_ooc(rowptr.data_ptr(), colidx.data_ptr(), vals.data_ptr(), m, n, nnz, k,
+                                _dev(W, torch.float32, "W"), _dev(H, torch.float32, "H"), iters, eps,
+                                batch_nnz, device_budget_bytes, _stream(stream)))
 
 
 def nmf_mu_dense_batched(n_runs, A, m, n, k, W, H, iters, eps, stream=None) -> None:

@@ -4,6 +4,7 @@
 #include "nmfmu.h"
 #include "nmfmu_internal.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -929,6 +930,149 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
         NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, W, c.gw, Ht, eps, st));   // H update on H^T
         NMF_HIP(launch_gram_w(Ht, n, k, c.gh, c.gpart, c.counters, st));
         NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st));        // W update
+    }
+    NMF_HIP(launch_transpose(Ht, n, k, H, st));
+    return NMF_OK;
+}
+
+// Out-of-memory CSR: row batches of about batch_nnz stored entries each, streamed from host
+// memory every sweep in the order of nmf_mu_ooc (W update of the batch with the current H, then
+// the batch's share of W^T A for the next H update).  A batch is a CSR matrix of its own once
+// its row pointers are made relative; its column-ordered copy is rebuilt on the device each
+// time (a sort of the batch, which runs beside the upload of the next one).
+int nmf_mu_csr_ooc(const int64_t *rowptr_host, const int32_t *colidx_host, const float *vals_host,
+                   int64_t m, int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t iters,
+                   float eps, int64_t batch_nnz, int64_t device_budget_bytes, void *stream)
+{
+    if (!rowptr_host) return fail(NMF_EINVAL, "null pointer%s");
+    if (nnz < 0) return fail(NMF_EINVAL, "nnz must be >= 0%s");
+    if (nnz > 0 && (!colidx_host || !vals_host)) return fail(NMF_EINVAL, "null pointer%s");
+    if (int rc = check_common(rowptr_host, W, H, m, n, k, iters, eps)) return rc;
+    if (batch_nnz < 1) return fail(NMF_EINVAL, "batch_nnz must be >= 1%s");
+    if (device_budget_bytes < 1) return fail(NMF_EINVAL, "device_budget_bytes must be >= 1%s");
+    if (m >= ((int64_t)1 << 31)) return fail(NMF_EUNSUPPORTED, "CSR path needs m < 2^31%s");
+    if (iters == 0) return NMF_OK;
+    if (rowptr_host[0] != 0 || rowptr_host[m] != nnz) return fail(NMF_EINVAL, "rowptr[0] != 0 or rowptr[m] != nnz%s");
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    // Row batches: as many whole rows as fit batch_nnz entries, at least one row.
+    struct Batch { int64_t r0, r1, e0, e1; };
+    std::vector<Batch> batches;
+    int64_t max_rows = 1, max_nnz = 1;
+    for (int64_t r0 = 0; r0 < m;) {
+        const int64_t e0 = rowptr_host[r0];
+        const int64_t *hi = std::upper_bound(rowptr_host + r0 + 1, rowptr_host + m + 1, e0 + batch_nnz);
+        int64_t r1 = (hi - rowptr_host) - 1;
+        if (r1 <= r0) r1 = r0 + 1;
+        const int64_t e1 = rowptr_host[r1];
+        if (e1 < e0) return fail(NMF_EINVAL, "rowptr is not non-decreasing%s");
+        if (e1 - e0 >= ((int64_t)1 << 31)) return fail(NMF_EUNSUPPORTED, "a row batch needs fewer than 2^31 entries%s");
+        batches.push_back({r0, r1, e0, e1});
+        if (r1 - r0 > max_rows) max_rows = r1 - r0;
+        if (e1 - e0 > max_nnz) max_nnz = e1 - e0;
+        r0 = r1;
+    }
+    const size_t rp_bytes = align_up((size_t)(max_rows + 1) * sizeof(int64_t));
+    const size_t ci_bytes = align_up((size_t)max_nnz * sizeof(int32_t));
+    const size_t va_bytes = align_up((size_t)max_nnz * sizeof(float));
+    const size_t slot_bytes = rp_bytes + ci_bytes + va_bytes;
+    int slots = (int)((size_t)device_budget_bytes / slot_bytes);
+    if (slots < 1) return fail(NMF_ENOMEM, "device budget does not hold one batch%s");
+    if (slots > 3) slots = 3;
+
+    std::lock_guard<std::mutex> lock(g.mu);
+    const size_t temp_bytes = csc_sort_temp_bytes(max_nnz, n);
+    const size_t need = common_bytes(k) + 2 * align_up((size_t)n * k * sizeof(float)) + rp_bytes +
+                        align_up((size_t)(n + 1) * sizeof(int64_t)) + 2 * ci_bytes + va_bytes +
+                        2 * align_up((size_t)max_nnz * sizeof(uint64_t)) + align_up(temp_bytes) +
+                        2 * align_up((size_t)(kCsrParts + 1) * sizeof(int64_t)) +
+                        2 * align_up((size_t)(max_nnz / kLongRow + 2) * sizeof(int32_t)) + kAlign;
+    void *ws = nullptr;
+    if (int rc = ensure_workspace(need, &ws)) return rc;
+    Carve cv(ws);
+    const Common c = carve_common(cv, k);
+    float *Ht = cv.take<float>((size_t)n * k);
+    float *Num = cv.take<float>((size_t)n * k);
+    int64_t *rowptr_loc = cv.take<int64_t>((size_t)max_rows + 1);
+    int64_t *colptr = cv.take<int64_t>((size_t)n + 1);
+    int32_t *rowidx = cv.take<int32_t>((size_t)max_nnz);
+    float *cvals = cv.take<float>((size_t)max_nnz);
+    int32_t *sorted_cols = cv.take<int32_t>((size_t)max_nnz);
+    uint64_t *payload = cv.take<uint64_t>((size_t)max_nnz);
+    uint64_t *sorted_payload = cv.take<uint64_t>((size_t)max_nnz);
+    char *sort_temp = cv.take<char>(temp_bytes);
+    int64_t *part_r = cv.take<int64_t>((size_t)kCsrParts + 1);
+    int64_t *part_c = cv.take<int64_t>((size_t)kCsrParts + 1);
+    int32_t *long_r = cv.take<int32_t>((size_t)(max_nnz / kLongRow + 2));
+    int32_t *long_c = cv.take<int32_t>((size_t)(max_nnz / kLongRow + 2));
+    unsigned *long_n = cv.take<unsigned>(64);
+    if (cv.off > need) return fail(NMF_EHIP, "internal: csr_ooc workspace accounting%s");
+
+    if (g.sl_stage_bytes < slots * slot_bytes) {
+        if (g.sl_stage) {
+            NMF_HIP(hipDeviceSynchronize());
+            NMF_HIP(hipFree(g.sl_stage));
+            g.sl_stage = nullptr;
+            g.sl_stage_bytes = 0;
+        }
+        hipError_t e = hipMalloc(&g.sl_stage, slots * slot_bytes);
+        if (e != hipSuccess) return fail(NMF_ENOMEM, "hipMalloc(staging): %s", hipGetErrorString(e));
+        g.sl_stage_bytes = slots * slot_bytes;
+    }
+    if (!g.copy_stream) NMF_HIP(hipStreamCreateWithFlags(&g.copy_stream, hipStreamNonBlocking));
+    if (!g.ev_entry) NMF_HIP(hipEventCreateWithFlags(&g.ev_entry, hipEventDisableTiming));
+    for (int i = 0; i < 3; ++i) {
+        if (!g.sl_copied[i]) NMF_HIP(hipEventCreateWithFlags(&g.sl_copied[i], hipEventDisableTiming));
+        if (!g.sl_freed[i]) NMF_HIP(hipEventCreateWithFlags(&g.sl_freed[i], hipEventDisableTiming));
+    }
+    NMF_HIP(hipEventRecord(g.ev_entry, st));
+    NMF_HIP(hipStreamWaitEvent(g.copy_stream, g.ev_entry, 0));
+
+    NMF_HIP(launch_transpose(H, k, n, Ht, st));
+    int64_t issued = 0;
+    for (int s = 0; s <= iters; ++s) {
+        if (s < iters) NMF_HIP(launch_fill_f32(Num, n * (int64_t)k, 0.f, st));
+        for (size_t b = 0; b < batches.size(); ++b, ++issued) {
+            const Batch &bt = batches[b];
+            const int64_t rows = bt.r1 - bt.r0, cnt = bt.e1 - bt.e0;
+            const int slot = (int)(issued % slots);
+            char *base = static_cast<char *>(g.sl_stage) + slot * slot_bytes;
+            int64_t *rp = reinterpret_cast<int64_t *>(base);
+            int32_t *ci = reinterpret_cast<int32_t *>(base + rp_bytes);
+            float *va = reinterpret_cast<float *>(base + rp_bytes + ci_bytes);
+            if (issued >= slots) NMF_HIP(hipStreamWaitEvent(g.copy_stream, g.sl_freed[slot], 0));
+            NMF_HIP(hipMemcpyAsync(rp, rowptr_host + bt.r0, (size_t)(rows + 1) * sizeof(int64_t),
+                                   hipMemcpyHostToDevice, g.copy_stream));
+            if (cnt > 0) {
+                NMF_HIP(hipMemcpyAsync(ci, colidx_host + bt.e0, (size_t)cnt * sizeof(int32_t),
+                                       hipMemcpyHostToDevice, g.copy_stream));
+                NMF_HIP(hipMemcpyAsync(va, vals_host + bt.e0, (size_t)cnt * sizeof(float),
+                                       hipMemcpyHostToDevice, g.copy_stream));
+            }
+            NMF_HIP(hipEventRecord(g.sl_copied[slot], g.copy_stream));
+            NMF_HIP(hipStreamWaitEvent(st, g.sl_copied[slot], 0));
+            NMF_HIP(launch_rebase_i64(rp, rows + 1, bt.e0, rowptr_loc, st));
+            float *Wb = W + bt.r0 * k;
+            if (s > 0) {
+                NMF_HIP(launch_csr_partition(rowptr_loc, rows, kCsrParts, part_r, st));
+                NMF_HIP(launch_csr_long_rows(rowptr_loc, rows, long_r, long_n, st));
+                NMF_HIP(launch_aht_csr(rowptr_loc, ci, va, part_r, long_r, long_n, k, Ht, c.gh, Wb, eps, st));
+            }
+            if (s < iters) {
+                NMF_HIP(launch_csc_build(rowptr_loc, ci, va, rows, n, cnt, sorted_cols, payload, sorted_payload,
+                                         sort_temp, temp_bytes, colptr, rowidx, cvals, st));
+                NMF_HIP(launch_csr_partition(colptr, n, kCsrParts, part_c, st));
+                NMF_HIP(launch_csr_long_rows(colptr, n, long_c, long_n + 1, st));
+                NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, Wb, nullptr, Num, eps,
+                                       st, true));
+            }
+            NMF_HIP(hipEventRecord(g.sl_freed[slot], st));
+        }
+        if (s < iters) {
+            NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+            NMF_HIP(launch_row_update(Ht, Num, c.gw, k, n, eps, st));
+            NMF_HIP(launch_gram_w(Ht, n, k, c.gh, c.gpart, c.counters, st));
+        }
     }
     NMF_HIP(launch_transpose(Ht, n, k, H, st));
     return NMF_OK;

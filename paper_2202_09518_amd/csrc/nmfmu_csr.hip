@@ -137,6 +137,8 @@ __device__ __forceinline__ float gather_chunk(const int32_t *__restrict__ colidx
 // Algorithm 3 in one kernel (the row of A H^T lives in one register per lane);
 // with the column-ordered copy, T = W, G = W^T W, X = Ht: WTA and the H update.
 // Wavefront gw works on rows [part[gw], part[gw + 1]), 64 / LPR rows at a time.
+// accumulate != 0: no update; the gathered sums are added to W instead (the
+// numerator of an update collected over several row batches of the matrix; GH unused).
 // ---------------------------------------------------------------------------
 template <int LPR>
 __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict__ rowptr,
@@ -145,11 +147,11 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
                                                       const int64_t *__restrict__ part, int k,
                                                       const float *__restrict__ Ht,
                                                       const float *__restrict__ GH, float *W,
-                                                      float eps)
+                                                      float eps, int accumulate)
 {
     constexpr int LDG = 65, RPW = 64 / LPR;
     __shared__ float Gs[64 * LDG];
-    stage_gram(Gs, GH, k, LDG);
+    if (!accumulate) stage_gram(Gs, GH, k, LDG);
     const int lane = threadIdx.x & 63;
     const int c = lane % LPR;
     const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -169,6 +171,10 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
             e += LPR;
         }
         const float w = (valid && c < k) ? W[row * k + c] : 0.f;
+        if (accumulate) {
+            if (valid && c < k) W[row * k + c] = w + acc;
+            continue;
+        }
         const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
         if (valid && c < k) W[row * k + c] = w * acc / den;
     }
@@ -185,14 +191,14 @@ __global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__rest
                                                            const unsigned *__restrict__ count, int k,
                                                            const float *__restrict__ Ht,
                                                            const float *__restrict__ GH, float *W,
-                                                           float eps)
+                                                           float eps, int accumulate)
 {
     constexpr int LDG = 65, NG = 256 / LPR;
     __shared__ float Gs[64 * LDG];
     __shared__ float part_acc[NG][LPR];
     const unsigned n_long = *count;
     if (n_long == 0) return;
-    stage_gram(Gs, GH, k, LDG);
+    if (!accumulate) stage_gram(Gs, GH, k, LDG);
     const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     for (unsigned li = blockIdx.x; li < n_long; li += gridDim.x) {
         const int64_t row = list[li];
@@ -212,11 +218,51 @@ __global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__rest
             const float tot = part_acc[0][c];
             const bool mine = threadIdx.x < LPR;
             const float w = (mine && c < k) ? W[row * k + c] : 0.f;
-            const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
-            if (mine && c < k) W[row * k + c] = w * tot / den;
+            if (accumulate) {
+                if (mine && c < k) W[row * k + c] = w + tot;
+            } else {
+                const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
+                if (mine && c < k) W[row * k + c] = w * tot / den;
+            }
         }
         __syncthreads();
     }
+}
+
+// X[i][:] <- X[i][:] * Num[i][:] / (X[i][:] G + eps) for i < rows: the update once its
+// numerator has been collected (out-of-memory CSR); lane group per row as above.
+template <int LPR>
+__global__ __launch_bounds__(256) void row_update_kernel(float *X, const float *__restrict__ Num,
+                                                         const float *__restrict__ G, int k,
+                                                         int64_t rows, float eps)
+{
+    constexpr int LDG = 65, RPW = 64 / LPR;
+    __shared__ float Gs[64 * LDG];
+    stage_gram(Gs, G, k, LDG);
+    const int lane = threadIdx.x & 63;
+    const int c = lane % LPR;
+    const int64_t waves = (int64_t)gridDim.x * 4;
+    for (int64_t base = ((int64_t)blockIdx.x * 4 + (threadIdx.x >> 6)) * RPW; base < rows; base += waves * RPW) {
+        const int64_t row = base + lane / LPR;
+        const bool valid = row < rows && c < k;
+        const float x = valid ? X[row * k + c] : 0.f;
+        const float den = row_times_gram<LPR>(x, Gs, LDG, k, c) + eps;
+        if (valid) X[row * k + c] = x * Num[row * k + c] / den;
+    }
+}
+
+// out[i] = in[i] - base: row pointers of a row batch made relative to the batch's first entry.
+__global__ __launch_bounds__(256) void rebase_i64_kernel(const int64_t *__restrict__ in, int64_t count,
+                                                         int64_t base, int64_t *__restrict__ out)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+        out[i] = in[i] - base;
+}
+
+__global__ __launch_bounds__(256) void fill_f32_kernel(float *p, int64_t count, float v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256)
+        p[i] = v;
 }
 
 // ---------------------------------------------------------------------------
@@ -322,14 +368,45 @@ hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list,
 
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
-                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st)
+                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
+                          bool accumulate)
 {
     const int lpr = lanes_per_row(k);
     const dim3 grid(kCsrParts / 4), block(256);
+    const int acc = accumulate ? 1 : 0;
     NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_kernel<L>), grid, block, 0, st, rowptr, colidx,
-                                             vals, part, k, Ht, GH, W, eps));
+                                             vals, part, k, Ht, GH, W, eps, acc));
     NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_long_kernel<L>), dim3(256), block, 0, st, rowptr,
-                                             colidx, vals, long_list, long_count, k, Ht, GH, W, eps));
+                                             colidx, vals, long_list, long_count, k, Ht, GH, W, eps, acc));
+    return hipGetLastError();
+}
+
+hipError_t launch_row_update(float *X, const float *Num, const float *G, int k, int64_t rows, float eps,
+                             hipStream_t st)
+{
+    const int lpr = lanes_per_row(k);
+    int64_t b = (rows * lpr / 64 + 3) / 4;
+    if (b > 8192) b = 8192;
+    if (b < 1) b = 1;
+    const dim3 grid((unsigned)b), block(256);
+    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((row_update_kernel<L>), grid, block, 0, st, X, Num, G, k, rows, eps));
+    return hipGetLastError();
+}
+
+hipError_t launch_rebase_i64(const int64_t *in, int64_t count, int64_t base, int64_t *out, hipStream_t st)
+{
+    int64_t b = (count + 255) / 256;
+    if (b > 4096) b = 4096;
+    hipLaunchKernelGGL(rebase_i64_kernel, dim3((unsigned)b), dim3(256), 0, st, in, count, base, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_f32(float *p, int64_t count, float v, hipStream_t st)
+{
+    int64_t b = (count + 255) / 256;
+    if (b > 8192) b = 8192;
+    if (b < 1) b = 1;
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)b), dim3(256), 0, st, p, count, v);
     return hipGetLastError();
 }
 

@@ -97,7 +97,15 @@ hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list,
                                 hipStream_t st);
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
-                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st);
+                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
+                          bool accumulate = false);
+// accumulate: X[i][:] += (gathered sum) instead of the update (GH unused).
+// X[i][:] <- X[i][:] * Num[i][:] / (X[i][:] G + eps), i < rows (X, Num rows x k).
+hipError_t launch_row_update(float *X, const float *Num, const float *G, int k, int64_t rows, float eps,
+                             hipStream_t st);
+// out[i] = in[i] - base, i < count.
+hipError_t launch_rebase_i64(const int64_t *in, int64_t count, int64_t base, int64_t *out, hipStream_t st);
+hipError_t launch_fill_f32(float *p, int64_t count, float v, hipStream_t st);
 // Column-ordered copy (colptr int64[n+1], rowidx int32[nnz], cvals float[nnz]) of a CSR matrix
 // by a stable sort on the column index.  Scratch: sorted_cols int32[nnz], payload and
 // sorted_payload uint64[nnz], sort_temp of csc_sort_temp_bytes(nnz, n) bytes.

@@ -579,6 +579,83 @@ def test_csr_skewed_rows_and_a_very_long_row():
     check(Wg, Hg, Wr, Hr, 2 * TOL1)
 
 
+def run_csr_ooc(rowptr, colidx, vals, m, n, W, H, iters, batch_nnz, budget=1 << 30, pinned=True):
+    k = W.shape[1]
+    rp = torch.from_numpy(np.ascontiguousarray(rowptr, dtype=np.int64))
+    ci = torch.from_numpy(np.ascontiguousarray(colidx, dtype=np.int32))
+    va = torch.from_numpy(np.ascontiguousarray(vals, dtype=np.float32))
+    if pinned:
+        rp, ci, va = rp.pin_memory(), ci.pin_memory(), va.pin_memory()
+    Wd, Hd = dev(W), dev(H)
+    nmf.nmf_mu_csr_ooc(rp, ci, va, m, n, int(vals.size), k, Wd, Hd, iters, EPS, batch_nnz, budget)
+    Wg, Hg = host(Wd), host(Hd)
+    assert np.array_equal(rp.numpy(), rowptr) and np.array_equal(ci.numpy(), colidx) and np.array_equal(va.numpy(), vals)
+    return Wg, Hg
+
+
+@pytest.mark.parametrize("m,n,k,density,iters,batch_nnz", [
+    (64, 48, 4, 0.3, 3, 100), (500, 700, 32, 0.05, 3, 3000), (1000, 300, 17, 0.02, 2, 1),
+    (300, 1000, 64, 0.05, 2, 10 ** 9), (2000, 1500, 33, 0.01, 2, 7777), (50, 60, 1, 0.5, 3, 64),
+])
+def test_csr_ooc_matches_oracle(m, n, k, density, iters, batch_nnz):
+    rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(m, n, density, seed=m + n))
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=m + n + 1))
+    Wg, Hg = run_csr_ooc(rowptr, colidx, vals, m, n, W, H, iters, batch_nnz)
+    Wr, Hr = orc.mu_csr(rowptr, colidx, vals, m, n, W, H, iters, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 1e-4 if iters > 1 else TOL1)
+
+
+def test_csr_ooc_one_batch_equals_resident_csr_bitwise_and_slots_do_not_matter():
+    rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(1500, 900, 0.02, seed=61))
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(1500, 900, 24, seed=62))
+    # several batches: the staging budget (1, 2 or 3 slots) does not change a bit
+    per_slot = 8 * 1501 + 8 * 5000 + 1024
+    ref = run_csr_ooc(rowptr, colidx, vals, 1500, 900, W, H, 3, 4000, budget=per_slot)
+    for slots in (2, 3):
+        got = run_csr_ooc(rowptr, colidx, vals, 1500, 900, W, H, 3, 4000, budget=slots * per_slot, pinned=slots == 2)
+        np.testing.assert_array_equal(ref[0], got[0])
+        np.testing.assert_array_equal(ref[1], got[1])
+    # one batch holding everything: the same sums in the same order as the resident CSR path
+    one = run_csr_ooc(rowptr, colidx, vals, 1500, 900, W, H, 3, 10 ** 9)
+    res = run_csr(rowptr, colidx, vals, 1500, 900, W, H, 3)
+    np.testing.assert_array_equal(one[0], res[0])
+    np.testing.assert_array_equal(one[1], res[1])
+
+
+def test_csr_ooc_skewed_rows_long_row_empty_rows_and_duplicates():
+    r = np.random.default_rng(91)
+    m, n, k = 300, 30000, 32
+    counts = np.minimum((r.pareto(1.2, m) * 8).astype(np.int64), n)
+    counts[7] = 20000            # above the long-row threshold: a batch of its own at batch_nnz = 5000
+    counts[8] = 0
+    counts[299] = 0              # the matrix ends in an empty row
+    rows = [np.sort(r.choice(n, int(c), replace=False)).astype(np.int32) for c in counts]
+    rows[3] = np.concatenate([rows[3], rows[3][:2]]) if rows[3].size >= 2 else rows[3]      # repeated (row, column)
+    counts[3] = rows[3].size
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(counts)
+    colidx = np.concatenate(rows).astype(np.int32)
+    vals = (1.0 - r.random(colidx.size, dtype=np.float32)).astype(np.float32)
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=92))
+    Wg, Hg = run_csr_ooc(rowptr, colidx, vals, m, n, W, H, 2, 5000)
+    Wr, Hr = orc.mu_csr(rowptr, colidx, vals, m, n, W, H, 2, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 2 * TOL1)
+    assert (Wg[8] == 0).all() and (Wg[299] == 0).all()
+
+
+def test_csr_ooc_argument_errors():
+    rp = torch.tensor([0, 1, 3], dtype=torch.int64)
+    ci = torch.tensor([0, 1, 2], dtype=torch.int32)
+    va = torch.ones(3)
+    W, H = torch.ones((2, 2), device="cuda"), torch.ones((2, 3), device="cuda")
+    with pytest.raises(nmf.NmfError) as e:
+        nmf.nmf_mu_csr_ooc(rp, ci, va, 2, 3, 4, 2, W, H, 1, EPS, 10, 1 << 20)       # rowptr[m] != nnz
+    assert e.value.status == nmf.NMF_EINVAL
+    with pytest.raises(nmf.NmfError) as e:
+        nmf.nmf_mu_csr_ooc(rp, ci, va, 2, 3, 3, 2, W, H, 1, EPS, 10, 8)             # budget below one batch
+    assert e.value.status == nmf.NMF_ENOMEM
+
+
 def test_csr_is_reproducible_run_to_run():
     rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(3000, 2000, 0.01, seed=98))
     W, H = (t.numpy() for t in nmf_inputs.init_factors(3000, 2000, 32, seed=99))
