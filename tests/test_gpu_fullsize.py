@@ -67,6 +67,15 @@ def test_config3_full_size_one_iteration():
     ew, eh = errs(W, H, Wr, Hr)
     say(f"config 3 full size, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
     assert max(ew, eh) < 1e-5
+    # the same matrix streamed from pinned host memory in batches of 32 Mi stored entries
+    # (the launch configuration of bench.py --workload c3ooc), against the same oracle result
+    rp, ci, va = rowptr.cpu().pin_memory(), colidx.cpu().pin_memory(), vals.cpu().pin_memory()
+    del rowptr, colidx, vals
+    W2, H2 = torch.from_numpy(W0).cuda(), torch.from_numpy(H0).cuda()
+    nmf.nmf_mu_csr_ooc(rp, ci, va, m, n, nnz, k, W2, H2, 1, EPS, 32 << 20, 2 << 30)
+    ew, eh = errs(W2, H2, Wr, Hr)
+    say(f"config 3 full size streamed from host memory, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 1e-5
 
 
 def test_config4_full_size_one_iteration_h_full_w_sampled():
