@@ -126,6 +126,22 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
                      int32_t *iters_done_host, double *residual_host, void *stream);
 
 /*
+ * nmf_mu_dense with the objective ||A - W H||_F reported after every iteration
+ * (Algorithm 1 evaluates it every iteration), at almost no cost: the norm is
+ * expanded as ||A||^2 - 2 <A H^T, W> + <H H^T, W^T W> and all three terms are
+ * by-products of the W update (its numerator against the new W, and the two
+ * Gram matrices); ||A||^2 is computed once per call.  The products are fp32
+ * sums, so the value carries an absolute error of about 2e-7 ||A||^2 / f: exact
+ * to 1e-4 relative while f >= 0.05 ||A||, a few percent at f = 0.005 ||A||;
+ * nmf_residual_dense gives the exact value (one more pass over A).  When the
+ * fast plan's workspace cannot be had, every value is the exact tiled one.
+ * objective_host: HOST memory, iters doubles.  Blocking.  W, H as nmf_mu_dense
+ * (bit-identical result).
+ */
+int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                         int32_t iters, float eps, double *objective_host, void *stream);
+
+/*
  * Resident sparse MU: the same iteration with A given in CSR (section 2.3
  * names the three CSR arrays: values, column indices, row pointers).
  *   rowptr  device, int64[m + 1], non-decreasing, rowptr[0] = 0, rowptr[m] = nnz

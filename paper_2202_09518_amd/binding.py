@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_csr_partition", "nmf_split_planes", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_mu_dense_tol.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
     L.nmf_mu_csr.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp]
     L.nmf_mu_ooc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
+    L.nmf_mu_dense_monitor.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_mu_csr_ooc.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
     L.nmf_mu_ooc_hostw.argtypes = [vp, vp, i64, i64, i32, vp, i32, f32, i64, i32, vp, vp]
     L.nmf_mu_dense_batched.argtypes = [i32, vp, i64, i64, vp, vp, vp, i32, f32, vp]
@@ -162,6 +163,14 @@ def nmf_mu_ooc_hostw(A_host, W_host, m, n, k, H, iters, eps, batch_rows, slots, 
     _check(lib().nmf_mu_ooc_hostw(A_host.data_ptr(), W_host.data_ptr(), m, n, k, _dev(H, torch.float32, "H"),
                                   iters, eps, batch_rows, slots, _stream(stream), ctypes.byref(used)))
     return int(used.value)
+
+
+def nmf_mu_dense_monitor(A, m, n, k, W, H, iters, eps, stream=None):
+    """Runs `iters` iterations; returns the objective after each (list of floats, blocking)."""
+    out = (ctypes.c_double * max(iters, 1))()
+    _check(lib().nmf_mu_dense_monitor(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
+                                      _dev(H, torch.float32, "H"), iters, eps, out, _stream(stream)))
+    return list(out)[:iters]
 
 
 def nmf_mu_csr_ooc(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, batch_nnz, device_budget_bytes,

@@ -197,13 +197,21 @@ int dense_workspace(int64_t m, int64_t n, int k, void **ws, bool *mirrored)
 
 constexpr int kDenseKernels = 6;
 
+// Per-iteration objective of a dense run (device memory): out[it] after iteration it.
+struct Monitor {
+    double *dpart;      // kFinMaxBlocks: <numerator, new W> per finisher block
+    double *normA2;     // [0] = ||A||_F^2, followed by 4096 doubles of scratch for its sum
+    double *out;        // iters values
+    double *res;        // direct plan: scratch of the tiled evaluation (ceil(m / 32) + 1 doubles)
+};
+
 // One resident dense run on `st`.  With `ev` (kDenseKernels * iters + 1 events)
 // an event is recorded before the first kernel of the loop and after every
 // kernel, for per-kernel timing; slots of kernels a plan does not use collapse
 // to zero duration.  `a_is_mirrored`: At already holds this A's transpose.
 int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, int iters,
                float eps, const DensePlan &p, hipStream_t st, bool a_is_mirrored = false,
-               hipEvent_t *ev = nullptr, const BlockMap *map = nullptr)
+               hipEvent_t *ev = nullptr, const BlockMap *map = nullptr, const Monitor *mon = nullptr)
 {
     const Common &c = p.c;
     // The plan may have been carved for a larger rank (stacks of an ensemble): split
@@ -234,8 +242,14 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.planes, true, p.ppart, s2, rps2, false, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, c.gh, nullptr, 0, c.gwp, k, m, eps, st, map, p.planes));
+            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, c.gh, nullptr, 0, c.gwp, k, m, eps, st, map, p.planes,
+                                         mon ? mon->dpart : nullptr));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            if (mon) {
+                // ||A - W H||_F from what this W update leaves behind: <A H^T, W>, H H^T, W^T W
+                NMF_HIP(launch_gram_sum(c.gwp, nbw, k, c.gw, st));
+                NMF_HIP(launch_objective(mon->dpart, nbw, c.gw, c.gh, k, mon->normA2, mon->out + it, st));
+            }
         }
         return NMF_OK;
     }
@@ -253,6 +267,7 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
         NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        if (mon) NMF_HIP(launch_residual(A, m, n, k, W, H, mon->res + 1, mon->out + it, st));   // exact, tiled
     }
     return NMF_OK;
 }
@@ -1145,6 +1160,41 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     }
     *iters_done_host = done;
     *residual_host = res;
+    return NMF_OK;
+}
+
+int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                         int32_t iters, float eps, double *objective_host, void *stream)
+{
+    if (int rc = check_common(A, W, H, m, n, k, iters, eps)) return rc;
+    if (!objective_host) return fail(NMF_EINVAL, "null pointer%s");
+    if (iters > (1 << 20)) return fail(NMF_EINVAL, "monitored run: iters <= 2^20%s");
+    if (iters == 0) return NMF_OK;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    std::lock_guard<std::mutex> lock(g.mu);
+    const size_t extra = align_up((size_t)kFinMaxBlocks * sizeof(double)) + align_up(4097 * sizeof(double)) +
+                         align_up((size_t)iters * sizeof(double)) + residual_scratch_bytes(m);
+    const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
+    void *ws = nullptr;
+    bool mirrored = false;
+    if ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK)) {
+        mirrored = true;
+    } else {
+        (void)hipGetLastError();
+        if (int rc = ensure_workspace(small, &ws)) return rc;
+    }
+    ws = g.ws;
+    const DensePlan p = carve_dense(ws, m, n, k, mirrored);
+    Carve cv(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
+    Monitor mon;
+    mon.dpart = cv.take<double>(kFinMaxBlocks);
+    mon.normA2 = cv.take<double>(4097);
+    mon.out = cv.take<double>((size_t)iters);
+    mon.res = cv.take<double>((size_t)(m + 31) / 32 + 1);
+    if (mirrored) NMF_HIP(launch_sumsq(A, m * n, mon.normA2 + 1, mon.normA2, st));
+    if (int rc = dense_body(A, m, n, k, W, H, iters, eps, p, st, false, nullptr, nullptr, &mon)) return rc;
+    NMF_HIP(hipMemcpyAsync(objective_host, mon.out, (size_t)iters * sizeof(double), hipMemcpyDeviceToHost, st));
+    NMF_HIP(hipStreamSynchronize(st));
     return NMF_OK;
 }
 

@@ -469,7 +469,8 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                                                             const float *__restrict__ Gfull,
                                                             const float *__restrict__ gin, int nbin,
                                                             float *__restrict__ gout,
-                                                            u32x4 *__restrict__ planes, int k,
+                                                            u32x4 *__restrict__ planes,
+                                                            double *__restrict__ dpart, int k,
                                                             int64_t len, float eps, BlockMap bm)
 {
     constexpr int NW = 8, KT = KP / 32 > 0 ? KP / 32 : 1, NC = (KP + 7) / 8, LD = KP + 1;
@@ -514,6 +515,7 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
         for (int b = 0; b < KT; ++b) acc[a][b] = f32x16{0};
 
     const int jl = lane, grp = w;
+    double dacc = 0.0;   // sum over this thread's entries of numerator x new value (objective monitor)
     const int64_t nchunks = (len + 63) >> 6;
     for (int64_t ch = blockIdx.x; ch < nchunks; ch += gridDim.x) {
         const int64_t j = ch * 64 + jl;
@@ -581,6 +583,7 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                     const int64_t at = (int64_t)c * len + j;
                     nv = X[at] * p[ci] / den;
                     X[at] = nv;
+                    dacc += (double)p[ci] * (double)nv;
                 }
                 Ts[jl * LDT + c] = nv;   // columns past the end contribute zeros
             }
@@ -629,6 +632,18 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                     }
                 }
             }
+        }
+    }
+    if (dpart) {
+        // <numerator, new X> of this block, summed in a fixed order (waves, then lanes by tree)
+        __shared__ double dsum[NW];
+        for (int off = 32; off > 0; off >>= 1) dacc += __shfl_xor(dacc, off);
+        if (lane == 0) dsum[w] = dacc;
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0.0;
+            for (int i = 0; i < NW; ++i) t += dsum[i];
+            dpart[blockIdx.x] = t;
         }
     }
     if (!gout) return;
@@ -873,6 +888,55 @@ __global__ void residual_finish_kernel(const double *__restrict__ partial, int64
     }
 }
 
+// partial[b] = sum of squares of a slice of X (double), for ||A||_F^2.
+__global__ __launch_bounds__(256) void sumsq_kernel(const float *__restrict__ X, int64_t count,
+                                                    double *__restrict__ partial)
+{
+    __shared__ double wsum[4];
+    double acc = 0.0;
+    for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256) {
+        const float v = X[e];
+        acc += (double)v * (double)v;
+    }
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
+// out[0] = sum of `count` partials in index order.
+__global__ void sum_f64_kernel(const double *__restrict__ partial, int64_t count, double *out)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        double s = 0.0;
+        for (int64_t i = 0; i < count; ++i) s += partial[i];
+        out[0] = s;
+    }
+}
+
+// Objective from quantities the W update leaves behind (the expansion of section 2.1's norm):
+// ||A - W H||_F^2 = ||A||_F^2 - 2 <A H^T, W> + <H H^T, W^T W>, with <A H^T, W> = sum of dpart
+// (numerator of the W update against the new W), GH = H H^T and GW = W^T W of the new factors.
+// out[0] = square root of that, clamped at zero.  One block.
+__global__ __launch_bounds__(256) void objective_kernel(const double *__restrict__ dpart, int nb,
+                                                        const float *__restrict__ GW,
+                                                        const float *__restrict__ GH, int k,
+                                                        const double *__restrict__ normA2, double *out)
+{
+    __shared__ double part[256];
+    double gg = 0.0;
+    for (int e = threadIdx.x; e < k * k; e += 256) gg += (double)GW[e] * (double)GH[e];
+    part[threadIdx.x] = gg;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double g2 = 0.0, dot = 0.0;
+        for (int i = 0; i < 256; ++i) g2 += part[i];
+        for (int b = 0; b < nb; ++b) dot += dpart[b];
+        const double f2 = normA2[0] - 2.0 * dot + g2;
+        out[0] = f2 > 0.0 ? sqrt(f2) : 0.0;
+    }
+}
+
 // P = sum over the row splits of the partial W^T A results (test entry point only).
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float *__restrict__ ppart,
                                                            int splits, int64_t count,
@@ -1043,7 +1107,7 @@ int factor_update_blocks(int64_t len)
 hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
                                 const float *Gfull, const float *gin, int nbin, float *gout, int k,
                                 int64_t len, float eps, hipStream_t st, const BlockMap *map,
-                                void *planes)
+                                void *planes, double *dpart)
 {
     u32x4 *pl = wta_uses_planes(k) ? static_cast<u32x4 *>(planes) : nullptr;
     BlockMap bm;
@@ -1054,11 +1118,11 @@ hipError_t launch_factor_update(float *X, float *Xt, const float *part, int spli
     if (blocks > 65535) blocks = 65535;
     const dim3 grid((unsigned)blocks), block(512);
     if (k <= 8)
-        hipLaunchKernelGGL((factor_update_kernel<8>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, k, len, eps, bm);
+        hipLaunchKernelGGL((factor_update_kernel<8>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, dpart, k, len, eps, bm);
     else if (k <= 32)
-        hipLaunchKernelGGL((factor_update_kernel<32>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, k, len, eps, bm);
+        hipLaunchKernelGGL((factor_update_kernel<32>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, dpart, k, len, eps, bm);
     else
-        hipLaunchKernelGGL((factor_update_kernel<64>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, k, len, eps, bm);
+        hipLaunchKernelGGL((factor_update_kernel<64>), grid, block, 0, st, X, Xt, part, splits, Gfull, gin, nbin, gout, pl, dpart, k, len, eps, bm);
     return hipGetLastError();
 }
 
@@ -1068,6 +1132,23 @@ hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, fl
     int64_t b = (count + 255) / 256;
     if (b > 4096) b = 4096;
     hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b), dim3(256), 0, st, ppart, splits, count, P, accumulate ? 1 : 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_sumsq(const float *X, int64_t count, double *partial, double *out, hipStream_t st)
+{
+    int64_t b = (count + 256 * 64 - 1) / (256 * 64);
+    if (b > 4096) b = 4096;
+    if (b < 1) b = 1;
+    hipLaunchKernelGGL(sumsq_kernel, dim3((unsigned)b), dim3(256), 0, st, X, count, partial);
+    hipLaunchKernelGGL(sum_f64_kernel, dim3(1), dim3(64), 0, st, partial, b, out);
+    return hipGetLastError();
+}
+
+hipError_t launch_objective(const double *dpart, int nb, const float *GW, const float *GH, int k,
+                            const double *normA2, double *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(objective_kernel, dim3(1), dim3(256), 0, st, dpart, nb, GW, GH, k, normA2, out);
     return hipGetLastError();
 }
 

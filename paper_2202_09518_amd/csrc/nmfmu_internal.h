@@ -66,7 +66,15 @@ hipError_t launch_mu_apply(float *X, const float *P, const float *D, float eps, 
 hipError_t launch_factor_update(float *X, float *Xt, const float *part, int splits,
                                 const float *Gfull, const float *gin, int nbin, float *gout, int k,
                                 int64_t len, float eps, hipStream_t st,
-                                const BlockMap *map = nullptr, void *planes = nullptr);
+                                const BlockMap *map = nullptr, void *planes = nullptr,
+                                double *dpart = nullptr);
+// dpart (with an updating launch): per block, the sum of numerator x new value over its entries
+// (factor_update_blocks(len) doubles when gout is given, else one per 64 columns).
+// out[0] = sum of squares of X[0 .. count) in double; partial: 4096 doubles of scratch.
+hipError_t launch_sumsq(const float *X, int64_t count, double *partial, double *out, hipStream_t st);
+// out[0] = sqrt(max(0, normA2[0] - 2 sum(dpart[0 .. nb)) + <GW, GH>)).
+hipError_t launch_objective(const double *dpart, int nb, const float *GW, const float *GH, int k,
+                            const double *normA2, double *out, hipStream_t st);
 int factor_update_blocks(int64_t len);
 // G (k x k, ld k) = sum of nb sets of partial tiles.
 hipError_t launch_gram_sum(const float *gpart, int nb, int k, float *G, hipStream_t st);

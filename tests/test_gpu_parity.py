@@ -185,6 +185,49 @@ def test_dense_on_a_side_stream_and_unaligned_views():
     check(host(Wd), host(Hd), Wr, Hr, 2e-5)
 
 
+def oracle_trajectory(A, W, H, iters):
+    eps = float(np.float32(EPS))
+    out = []
+    for _ in range(iters):
+        W, H = orc.mu_dense(A, W, H, 1, eps)
+        out.append(orc.residual_dense(A, W, H))
+    return np.array(out), W, H
+
+
+@pytest.mark.parametrize("m,n,k,iters", [(256, 192, 4, 30), (1000, 520, 32, 6), (513, 260, 64, 4), (300, 200, 17, 5)])
+def test_monitor_reports_the_objective_of_every_iteration(m, n, k, iters):
+    if (m, n, k) == (256, 192, 4):
+        A, W, H = config1()
+    else:
+        A, W, H = case(m, n, k, 44)
+    want, Wr, Hr = oracle_trajectory(A, W, H, iters)
+    Wd, Hd = dev(W), dev(H)
+    got = np.array(nmf.nmf_mu_dense_monitor(dev(A), m, n, k, Wd, Hd, iters, EPS))
+    normA2 = float(np.sum(A.astype(np.float64) ** 2))
+    # fp32 sums in the three terms of the expansion: absolute error of f^2 about 3e-7 ||A||^2
+    bound = np.maximum(1e-5 * want, 3e-7 * normA2 / want)
+    assert (np.abs(got - want) <= bound).all(), (got, want)
+    assert (np.diff(got) <= 1e-6 * got[:-1] + 2 * bound[1:]).all()        # non-increasing, as the method guarantees
+    # the monitored run is the plain run, bit for bit
+    Wg, Hg = run_dense(A, W, H, iters)
+    np.testing.assert_array_equal(host(Wd), Wg)
+    np.testing.assert_array_equal(host(Hd), Hg)
+
+
+def test_monitor_small_plan_gives_the_exact_values():
+    A, W, H = case(300, 200, 9, 45)
+    want, _, _ = oracle_trajectory(A, W, H, 4)
+    need = nmf.nmf_mu_workspace_bytes(4, 300, 200, 0, 9, 0) + (1 << 16)
+    assert need < nmf.nmf_mu_workspace_bytes(0, 300, 200, 0, 9, 0)
+    buf = torch.empty(need, dtype=torch.uint8, device="cuda")
+    nmf.nmf_mu_set_workspace(buf)
+    try:
+        got = np.array(nmf.nmf_mu_dense_monitor(dev(A), 300, 200, 9, dev(W), dev(H), 4, EPS))
+    finally:
+        nmf.nmf_mu_set_workspace(None)
+    assert (np.abs(got - want) <= 1e-5 * want).all()
+
+
 # ---- operand encoding of the k <= 32 pass (bit-exact) ---------------------------------
 
 def bf16_bits_to_f64(u16):
