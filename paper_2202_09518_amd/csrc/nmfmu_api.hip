@@ -71,6 +71,7 @@ struct Common {
     unsigned *counters;
     float *gw, *gh, *gpart;
     float *gwp, *ghp;   // partial Gram tiles handed from one finisher to the next
+    float *gws, *ghs;   // the same, added up in groups by the pass that runs in between
 };
 
 Common carve_common(Carve &c, int k)
@@ -83,6 +84,8 @@ Common carve_common(Carve &c, int k)
     r.gpart = c.take<float>((size_t)kGramMaxBlocks * kt * kt * 1024);
     r.gwp = c.take<float>((size_t)kFinMaxBlocks * kt * kt * 1024);
     r.ghp = c.take<float>((size_t)kFinMaxBlocks * kt * kt * 1024);
+    r.gws = c.take<float>((size_t)(kFinMaxBlocks / kGramGroup) * kt * kt * 1024);
+    r.ghs = c.take<float>((size_t)(kFinMaxBlocks / kGramGroup) * kt * kt * 1024);
     return r;
 }
 
@@ -231,23 +234,26 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
         NMF_HIP(launch_factor_update(p.Wt, nullptr, nullptr, 0, nullptr, nullptr, 0, c.gwp, k, m, eps, st, nullptr, p.planes));
         const int nbw = factor_update_blocks(m), nbh = factor_update_blocks(n);
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        // The tiles of a finisher are needed, summed, by the next finisher; the pass that runs
+        // in between adds them up in groups of kGramGroup on the side (its first workgroups),
+        // the finisher sums the few group sets while it stages G: no launch of its own.
+        const int ngw = gram_groups(nbw), ngh = gram_groups(nbh);
         for (int it = 0; it < iters; ++it) {
-            NMF_HIP(launch_gram_sum(c.gwp, nbw, k, c.gw, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_wta_pass(A, m, n, k, W, p.planes, true, p.ppart, s1, rps1, false, st));
+            NMF_HIP(launch_wta_pass(A, m, n, k, W, p.planes, true, p.ppart, s1, rps1, false, st, c.gwp, nbw, c.gws));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, s1, c.gw, nullptr, 0, c.ghp, k, n, eps, st, map, p.planes));
+            NMF_HIP(launch_factor_update(H, p.Ht, p.ppart, s1, nullptr, c.gws, ngw, c.ghp, k, n, eps, st, map, p.planes));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_gram_sum(c.ghp, nbh, k, c.gh, st));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.planes, true, p.ppart, s2, rps2, false, st));
+            NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.planes, true, p.ppart, s2, rps2, false, st, c.ghp, nbh, c.ghs));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, c.gh, nullptr, 0, c.gwp, k, m, eps, st, map, p.planes,
+            NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, nullptr, c.ghs, ngh, c.gwp, k, m, eps, st, map, p.planes,
                                          mon ? mon->dpart : nullptr));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             if (mon) {
                 // ||A - W H||_F from what this W update leaves behind: <A H^T, W>, H H^T, W^T W
                 NMF_HIP(launch_gram_sum(c.gwp, nbw, k, c.gw, st));
+                NMF_HIP(launch_gram_sum(c.ghs, ngh, k, c.gh, st));
                 NMF_HIP(launch_objective(mon->dpart, nbw, c.gw, c.gh, k, mon->normA2, mon->out + it, st));
             }
         }

@@ -211,6 +211,34 @@ __global__ __launch_bounds__(512) void gram_kernel(const float *__restrict__ X, 
     if (tid == 0) counters[blockIdx.y] = 0u;
 }
 
+// Side job of the pass kernels: the Gram tiles a finisher left behind (nsets sets of
+// kt x kt tiles of 1024 floats) are needed, summed, by the finisher AFTER this pass.  The
+// first workgroups of the pass add them up in groups of kGramGroup sets (in set order) so
+// that the finisher has at most kFinMaxBlocks / kGramGroup sets to sum and no separate
+// launch is needed.  Job j = a quarter of the entries of group j / 4, dealt to the workgroups in order.
+__device__ __forceinline__ void sum_tile_groups(const float *__restrict__ gtiles, int nsets, int k,
+                                                float *__restrict__ gsum)
+{
+    const int ngroups = (nsets + kGramGroup - 1) / kGramGroup;
+    const int kt = (k + 31) >> 5;
+    const int stride = kt * kt * 1024;
+    const int nwg = gridDim.x * gridDim.y;
+    for (int job = blockIdx.y * gridDim.x + blockIdx.x; job < 4 * ngroups; job += nwg) {
+        const int group = job >> 2, quarter = job & 3;
+        const int first = group * kGramGroup;
+        const int count = (nsets - first < kGramGroup) ? nsets - first : kGramGroup;
+        for (int e = quarter * (stride / 4) + threadIdx.x; e < (quarter + 1) * (stride / 4); e += blockDim.x) {
+            float t[kGramGroup];
+#pragma unroll
+            for (int b = 0; b < kGramGroup; ++b) t[b] = gtiles[(int64_t)(first + (b < count ? b : 0)) * stride + e];
+            float sum = 0.f;
+#pragma unroll
+            for (int b = 0; b < kGramGroup; ++b) sum += (b < count) ? t[b] : 0.f;
+            gsum[(int64_t)group * stride + e] = sum;
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // W^T A pass.  Workgroup = 4 waves on one 128-column slab of A and one row
 // split; wave w takes row pairs w, w+4, ... of the split.  Per row pair a lane
@@ -229,11 +257,14 @@ __global__ __launch_bounds__(64 * kWtaWaves, OCC) void wta_pass_kernel(const flo
                                                        const float *__restrict__ W,
                                                        float *__restrict__ ppart, int64_t rows,
                                                        int64_t n, int k, int64_t rps,
-                                                       int accumulate)
+                                                       int accumulate,
+                                                       const float *__restrict__ gtiles, int nsets,
+                                                       float *__restrict__ gsum)
 {
     constexpr int NW = kWtaWaves;
     constexpr int LD = 132;
     __shared__ float red[KT * 32 * LD];
+    if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int jj = lane & 31, half = lane >> 5;
     const int64_t j0 = (int64_t)blockIdx.x * kWtaCols;
@@ -356,11 +387,13 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
 template <bool VEC>
 __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_kernel(
     const float *__restrict__ A, const u32x4 *__restrict__ planes, float *__restrict__ ppart,
-    int64_t rows, int64_t n, int k, int64_t rps, int accumulate)
+    int64_t rows, int64_t n, int k, int64_t rps, int accumulate,
+    const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum)
 {
     constexpr int NW = kWtaWaves;
     constexpr int LD = 132;
     __shared__ float red[32 * LD];
+    if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int jj = lane & 31, half = lane >> 5;
     const int64_t j0 = (int64_t)blockIdx.x * kWtaCols;
@@ -415,6 +448,126 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_kernel(
             acc[q] = mfma_bf16(cur.wt[0], at[0], acc[q]);
         }
         cur = nxt;
+    }
+
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    const int idx = acc_row(v, half) * LD + q * 32 + jj;
+                    if (ww == 0) red[idx] = acc[q][v];
+                    else red[idx] += acc[q][v];
+                }
+        }
+        __syncthreads();
+    }
+    float *dst = ppart + (int64_t)blockIdx.y * k * n;
+    for (int e = tid; e < k * kWtaCols; e += 64 * NW) {
+        const int c = e >> 7, x = e & 127;
+        const int64_t cj = j0 + x;
+        if (cj < n) {
+            float val = red[c * LD + (x & 3) * 32 + (x >> 2)];
+            float *p = dst + (int64_t)c * n + cj;
+            if (accumulate) val += *p;
+            *p = val;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The same pass for 16-byte aligned A with n % 4 == 0 and 64 n < 2^31, on buffer
+// loads: per 16-row step a wave builds one descriptor over those rows (base
+// A + first row, extent = the rows that exist in this split) and every lane
+// loads row r at byte offset (8 half + r) * 4 n + 4 col from it.  Rows past the
+// end of the split are outside the extent and read as zero, without a compare
+// or select per load, and the addresses cost one VALU add per load.  The planes
+// are read the same way (extent = the 8-row groups that exist).  Two steps are
+// written out so that the staging registers alternate without copies.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
+    const float *__restrict__ A, const u32x4 *__restrict__ planes, float *__restrict__ ppart,
+    int64_t rows, int64_t n, int k, int64_t rps, int accumulate,
+    const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum)
+{
+    constexpr int NW = kWtaWaves;
+    constexpr int LD = 132;
+    constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+    __shared__ float red[32 * LD];
+    if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int jj = lane & 31, half = lane >> 5;
+    const int64_t j0 = (int64_t)blockIdx.x * kWtaCols;
+    int64_t col = j0 + 4 * jj;
+    if (col >= n) col = 0;   // lanes past the edge read valid data that is never stored
+    const int64_t r0 = (int64_t)blockIdx.y * rps;
+    const int64_t r1 = (r0 + rps < rows) ? r0 + rps : rows;
+    const unsigned rowb = (unsigned)(n * 4);
+    const unsigned loff = (unsigned)(half * 8) * rowb + (unsigned)col * 4;
+    const unsigned poff = (unsigned)(half * 3 * 32 + jj) * 16;
+    const int64_t ngroups = (rows + 7) >> 3;
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int q = 0; q < 4; ++q) acc[q] = f32x16{0};
+
+    struct Stage {
+        u32x4 a[8];
+        u32x4 wt[3];
+    };
+    auto load_stage = [&](Stage &s, int64_t ib) {
+        int64_t av = r1 - ib;                       // rows of this step inside the split
+        av = av < 0 ? 0 : (av > 16 ? 16 : av);
+        const int64_t g = ib >> 3;
+        int64_t ng = av ? ngroups - g : 0;          // 8-row groups of planes that exist
+        ng = ng < 0 ? 0 : (ng > 2 ? 2 : ng);
+        const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(A + (av ? ib : 0) * n), 0, (int)(av * rowb), kRsrcFlags);
+        const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<u32x4 *>(planes + (ng ? g : 0) * 3 * 32), 0, (int)(ng * 3 * 32 * 16), kRsrcFlags);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b128(ra, loff + r * rowb, 0, 0);
+#pragma unroll
+        for (int pl = 0; pl < 3; ++pl) s.wt[pl] = __builtin_amdgcn_raw_buffer_load_b128(rp, poff + pl * 32 * 16, 0, 0);
+    };
+    auto compute = [&](const Stage &c) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            u32x4 at[3];
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                unsigned h0, m0, l0, h1, m1, l1;
+                split3(__uint_as_float(c.a[2 * pr][q]), h0, m0, l0);
+                split3(__uint_as_float(c.a[2 * pr + 1][q]), h1, m1, l1);
+                at[0][pr] = pack2(h0, h1);
+                at[1][pr] = pack2(m0, m1);
+                at[2][pr] = pack2(l0, l1);
+            }
+            acc[q] = mfma_bf16(c.wt[2], at[2], acc[q]);
+            acc[q] = mfma_bf16(c.wt[2], at[1], acc[q]);
+            acc[q] = mfma_bf16(c.wt[1], at[2], acc[q]);
+            acc[q] = mfma_bf16(c.wt[2], at[0], acc[q]);
+            acc[q] = mfma_bf16(c.wt[1], at[1], acc[q]);
+            acc[q] = mfma_bf16(c.wt[0], at[2], acc[q]);
+            acc[q] = mfma_bf16(c.wt[1], at[0], acc[q]);
+            acc[q] = mfma_bf16(c.wt[0], at[1], acc[q]);
+            acc[q] = mfma_bf16(c.wt[0], at[0], acc[q]);
+        }
+    };
+    const int64_t step = 16 * NW;
+    Stage s0, s1;
+    int64_t i = r0 + 16 * w;
+    load_stage(s0, i);
+    while (i < r1) {
+        load_stage(s1, i + step);
+        compute(s0);
+        i += step;
+        if (i >= r1) break;
+        load_stage(s0, i + step);
+        compute(s1);
+        i += step;
     }
 
     for (int ww = 0; ww < NW; ++ww) {
@@ -1021,14 +1174,15 @@ hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *g
 
 template <int KT>
 static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *W,
-                         float *ppart, int64_t rows, int64_t n, int k, int64_t rps, int acc)
+                         float *ppart, int64_t rows, int64_t n, int k, int64_t rps, int acc,
+                         const float *gtiles, int nsets, float *gsum)
 {
     constexpr int U = 5, OCC = 2;
     const dim3 block(64 * kWtaWaves);
     if (vec)
-        hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, true>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);
+        hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, true>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
     else
-        hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, false>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc);
+        hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, false>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
 }
 
 size_t planes_bytes(int64_t rows) { return (size_t)((rows + 7) / 8) * 3 * 32 * 16; }
@@ -1060,7 +1214,7 @@ hipError_t launch_mu_apply(float *X, const float *P, const float *D, float eps, 
 
 hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
                            void *planes, bool planes_ready, float *ppart, int splits, int64_t rps,
-                           bool accumulate, hipStream_t st)
+                           bool accumulate, hipStream_t st, const float *gtiles, int nsets, float *gsum)
 {
     dim3 grid((unsigned)((n + kWtaCols - 1) / kWtaCols), (unsigned)splits);
     const bool vec = vec_ok(A, n);
@@ -1075,13 +1229,15 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
         }
         const u32x4 *pl = static_cast<const u32x4 *>(planes);
         const dim3 block(64 * kWtaWaves);
-        if (vec)
-            hipLaunchKernelGGL((wta_pass_split_kernel<true>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc);
+        if (vec && n < ((int64_t)1 << 25))
+            hipLaunchKernelGGL(wta_pass_split_buf_kernel, grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
+        else if (vec)
+            hipLaunchKernelGGL((wta_pass_split_kernel<true>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
         else
-            hipLaunchKernelGGL((wta_pass_split_kernel<false>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc);
+            hipLaunchKernelGGL((wta_pass_split_kernel<false>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
         break;
     }
-    case 2: wta_dispatch<2>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc); break;
+    case 2: wta_dispatch<2>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -16,6 +16,7 @@ constexpr int kAhtWaves = 8;        // waves per workgroup in the A H^T pass
 constexpr int kAhtRowTiles = 2;     // 32-row tiles per workgroup in that pass
 constexpr int kGramMaxBlocks = 64;  // partial Gram matrices before the final sum
 constexpr int kFinMaxBlocks = 256;  // finisher blocks when they also emit Gram partials
+constexpr int kGramGroup = 16;      // sets of Gram tiles added up per group by the following pass
 constexpr int kMaxKTiles = 2;       // 32-wide rank tiles: k <= 64
 
 inline int k_tiles(int k) { return (k + 31) / 32; }
@@ -52,7 +53,11 @@ hipError_t launch_split_planes_slice(const float *X, int64_t rows, int64_t ld, i
 // already holds the planes of W, otherwise they are produced first.
 hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const float *W,
                            void *planes, bool planes_ready, float *ppart, int splits,
-                           int64_t rows_per_split, bool accumulate, hipStream_t st);
+                           int64_t rows_per_split, bool accumulate, hipStream_t st,
+                           const float *gtiles = nullptr, int nsets = 0, float *gsum = nullptr);
+// gtiles (optional): nsets sets of partial Gram tiles for rank k that the first workgroups of
+// the pass add up in groups of kGramGroup into gsum (gram_groups(nsets) sets).
+inline int gram_groups(int nsets) { return (nsets + kGramGroup - 1) / kGramGroup; }
 // P[e] (+)= sum_s ppart[s][e], e < count.
 hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
                                hipStream_t st, bool accumulate = false);
