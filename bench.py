@@ -145,11 +145,17 @@ def bench_c3(args, torch, nmf, nmf_inputs):
     ms_step = (t1 - t0) * 1e3 / args.steps
     bytes_a = 2 * (8 * nnz + 8 * (m + 1))       # both passes read values, column indices, row pointers
     gbs = bytes_a / (ms_step * 1e-3) / 1e9
+    gather = 2 * nnz * k * 4 + bytes_a
     return {"metric": "MU iterations/s (CSR fp32)", "value": 1e3 / ms_step, "unit": "iterations/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
             "config": {"workload": f"c3: CSR {m}x{n}, nnz={nnz}, k={k}", "nnz": nnz},
-            "gbs_over_A": gbs, "frac_hbm_peak_over_A": gbs / HBM_PEAK_GBS}
+            "gbs_over_A": gbs, "frac_hbm_peak_over_A": gbs / HBM_PEAK_GBS,
+            # what the two gathers move: one k-float row of a factor per stored entry and product
+            # (the tables, 128 MiB and 512 MiB here, do not fit the 4 MiB of L2 an XCD has)
+            "roofline": {"bound": "hbm", "kernel": "aht_csr_kernel", "achieved": gather / (ms_step * 1e-3) / 1e9,
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gather / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                         "traffic": None, "algorithmic_bytes_per_iteration": gather}}
 
 
 def bench_c3ooc(args, torch, nmf, nmf_inputs):

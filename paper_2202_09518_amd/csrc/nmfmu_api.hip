@@ -947,9 +947,9 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
 
     NMF_HIP(launch_transpose(H, k, n, Ht, st));
     for (int it = 0; it < iters; ++it) {
-        NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+        NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
         NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, W, c.gw, Ht, eps, st));   // H update on H^T
-        NMF_HIP(launch_gram_w(Ht, n, k, c.gh, c.gpart, c.counters, st));
+        NMF_HIP(launch_gram_w_wide(Ht, n, k, c.gh, c.ghp, st));
         NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st));        // W update
     }
     NMF_HIP(launch_transpose(Ht, n, k, H, st));
@@ -1090,9 +1090,9 @@ int nmf_mu_csr_ooc(const int64_t *rowptr_host, const int32_t *colidx_host, const
             NMF_HIP(hipEventRecord(g.sl_freed[slot], st));
         }
         if (s < iters) {
-            NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+            NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
             NMF_HIP(launch_row_update(Ht, Num, c.gw, k, n, eps, st));
-            NMF_HIP(launch_gram_w(Ht, n, k, c.gh, c.gpart, c.counters, st));
+            NMF_HIP(launch_gram_w_wide(Ht, n, k, c.gh, c.ghp, st));
         }
     }
     NMF_HIP(launch_transpose(Ht, n, k, H, st));

@@ -1160,6 +1160,17 @@ hipError_t launch_gram_w(const float *X, int64_t rows, int k, float *G, float *g
     return hipGetLastError();
 }
 
+hipError_t launch_gram_w_wide(const float *X, int64_t rows, int k, float *G, float *tiles, hipStream_t st)
+{
+    const int kt = k_tiles(k);
+    int64_t nb = (rows + 511) / 512;
+    if (nb > kFinMaxBlocks) nb = kFinMaxBlocks;
+    if (nb < 1) nb = 1;
+    hipLaunchKernelGGL((gram_kernel<0, false>), dim3((unsigned)nb, kt * kt), dim3(512), 0, st, X, rows, k,
+                       static_cast<float *>(nullptr), tiles, static_cast<unsigned *>(nullptr));
+    return launch_gram_sum(tiles, (int)nb, k, G, st);
+}
+
 hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *gpart,
                          unsigned *counters, hipStream_t st)
 {
@@ -1229,10 +1240,9 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
         }
         const u32x4 *pl = static_cast<const u32x4 *>(planes);
         const dim3 block(64 * kWtaWaves);
+        // buffer loads address 16 rows with 32-bit offsets: 64 n bytes must stay below 2^31
         if (vec && n < ((int64_t)1 << 25))
             hipLaunchKernelGGL(wta_pass_split_buf_kernel, grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
-        else if (vec)
-            hipLaunchKernelGGL((wta_pass_split_kernel<true>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
         else
             hipLaunchKernelGGL((wta_pass_split_kernel<false>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
         break;

@@ -37,6 +37,9 @@ int64_t wta_rows_per_split(int64_t rows, int splits);
 // G (k x k, ld k) = X^T X for X rows x k (row-major, ld k).
 hipError_t launch_gram_w(const float *X, int64_t rows, int k, float *G, float *gpart,
                          unsigned *counters, hipStream_t st);
+// The same for a long factor (millions of rows): up to kFinMaxBlocks blocks write partial tiles
+// (tiles: kFinMaxBlocks sets), summed by launch_gram_sum.
+hipError_t launch_gram_w_wide(const float *X, int64_t rows, int k, float *G, float *tiles, hipStream_t st);
 // G (k x k, ld k) = X X^T for X k x cols (row-major, ld cols).
 hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *gpart,
                          unsigned *counters, hipStream_t st);
