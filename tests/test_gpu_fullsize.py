@@ -23,6 +23,20 @@ EPS = 1e-16
 EPSD = float(np.float32(EPS))
 
 
+@pytest.fixture(autouse=True)
+def release_memory_between_tests():
+    """The cases here hold tens of GiB of pinned host and device memory each: give the library's
+    workspace and torch's cached blocks (device and pinned host) back after every test."""
+    yield
+    import gc
+    gc.collect()
+    torch.cuda.synchronize()
+    nmf.nmf_mu_release()
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+
+
 def say(msg):
     print(msg, file=sys.stderr, flush=True)
 
