@@ -117,7 +117,10 @@ int nmf_residual_dense(const float *A, int64_t m, int64_t n, int32_t k,
  * Algorithm 1 with its stopping rule read as: iterate until ||A - W H||_F <= tol
  * or max_iters iterations have run.  The objective is evaluated before the first
  * iteration and then after every `check_every` iterations (each evaluation is
- * one more pass over A and a stream synchronisation).  On return
+ * one more pass over A and a stream synchronisation; with the fast plan the
+ * checks after iterations first use the expansion of nmf_mu_dense_monitor, which
+ * costs no pass, and fall back to the exact evaluation only when that value is
+ * within its error bound of tol, so the stopping decision is the exact one).  On return
  * *iters_done_host iterations have been applied to W, H and *residual_host is
  * the objective of the returned factors.  Blocking.
  */

@@ -206,6 +206,7 @@ struct Monitor {
     double *normA2;     // [0] = ||A||_F^2, followed by 4096 doubles of scratch for its sum
     double *out;        // iters values
     double *res;        // direct plan: scratch of the tiled evaluation (ceil(m / 32) + 1 doubles)
+    bool last_only;     // only the last iteration of the call reports (into out[0])
 };
 
 // One resident dense run on `st`.  With `ev` (kDenseKernels * iters + 1 events)
@@ -247,14 +248,16 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
             NMF_HIP(launch_wta_pass(p.At, n, m, k, p.Ht, p.planes, true, p.ppart, s2, rps2, false, st, c.ghp, nbh, c.ghs));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            const bool report = mon && (!mon->last_only || it == iters - 1);
             NMF_HIP(launch_factor_update(p.Wt, W, p.ppart, s2, nullptr, c.ghs, ngh, c.gwp, k, m, eps, st, map, p.planes,
-                                         mon ? mon->dpart : nullptr));
+                                         report ? mon->dpart : nullptr));
             if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-            if (mon) {
+            if (report) {
                 // ||A - W H||_F from what this W update leaves behind: <A H^T, W>, H H^T, W^T W
                 NMF_HIP(launch_gram_sum(c.gwp, nbw, k, c.gw, st));
                 NMF_HIP(launch_gram_sum(c.ghs, ngh, k, c.gh, st));
-                NMF_HIP(launch_objective(mon->dpart, nbw, c.gw, c.gh, k, mon->normA2, mon->out + it, st));
+                NMF_HIP(launch_objective(mon->dpart, nbw, c.gw, c.gh, k, mon->normA2,
+                                         mon->out + (mon->last_only ? 0 : it), st));
             }
         }
         return NMF_OK;
@@ -273,7 +276,8 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
         NMF_HIP(launch_aht_pass(A, m, n, k, H, c.gh, W, eps, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
         if (ev) NMF_HIP(hipEventRecord(*ev++, st));
-        if (mon) NMF_HIP(launch_residual(A, m, n, k, W, H, mon->res + 1, mon->out + it, st));   // exact, tiled
+        if (mon && (!mon->last_only || it == iters - 1))   // exact, tiled
+            NMF_HIP(launch_residual(A, m, n, k, W, H, mon->res + 1, mon->out + (mon->last_only ? 0 : it), st));
     }
     return NMF_OK;
 }
@@ -1141,8 +1145,9 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
     bool mirrored = false;
-    // the residual scratch rides behind whichever dense plan fits
-    const size_t extra = residual_scratch_bytes(m);
+    // the residual scratch and the monitor's few doubles ride behind whichever dense plan fits
+    const size_t extra = residual_scratch_bytes(m) + align_up((size_t)kFinMaxBlocks * sizeof(double)) +
+                         align_up(4097 * sizeof(double)) + kAlign;
     const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
     if ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK)) {
         mirrored = true;
@@ -1152,18 +1157,50 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     }
     ws = g.ws;
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
-    double *scratch = reinterpret_cast<double *>(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
+    Carve cv(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
+    double *scratch = cv.take<double>((size_t)(m + 31) / 32 + 1);
+    Monitor mon;
+    mon.dpart = cv.take<double>(kFinMaxBlocks);
+    mon.normA2 = cv.take<double>(4097);
+    mon.out = cv.take<double>(1);
+    mon.res = scratch;
+    mon.last_only = true;
     int done = 0;
     double res = 0.0;
+    bool exact = true;       // `res` comes from the tiled evaluation (not from the expansion)
     if (int rc = residual_to_host(A, m, n, k, W, H, scratch, &res, st)) return rc;
+    double normA2 = 0.0;
+    if (mirrored && max_iters > 0 && res > tol) {
+        NMF_HIP(launch_sumsq(A, m * n, mon.normA2 + 1, mon.normA2, st));
+        NMF_HIP(hipMemcpyAsync(&normA2, mon.normA2, sizeof(double), hipMemcpyDeviceToHost, st));
+        NMF_HIP(hipStreamSynchronize(st));
+    }
     bool have_at = false;
     while (done < max_iters && res > tol) {
         const int chunk = (max_iters - done < check_every) ? max_iters - done : check_every;
-        if (int rc = dense_body(A, m, n, k, W, H, chunk, eps, p, st, have_at)) return rc;
+        if (int rc = dense_body(A, m, n, k, W, H, chunk, eps, p, st, have_at, nullptr, nullptr, mirrored ? &mon : nullptr))
+            return rc;
         have_at = mirrored;
         done += chunk;
+        if (mirrored) {
+            // The objective of the chunk's last iteration from the by-products of its W update
+            // (no pass over A); its error is bounded by the fp32 sums of its three terms.  Only
+            // when it comes within that bound of the tolerance is the exact value needed.
+            double approx = 0.0;
+            NMF_HIP(hipMemcpyAsync(&approx, mon.out, sizeof(double), hipMemcpyDeviceToHost, st));
+            NMF_HIP(hipStreamSynchronize(st));
+            const double slack = 1e-3 * approx + 2e-6 * normA2 / (approx > 1e-300 ? approx : 1e-300);
+            if (approx > tol + slack) {
+                res = approx;
+                exact = false;
+                continue;
+            }
+        }
         if (int rc = residual_to_host(A, m, n, k, W, H, scratch, &res, st)) return rc;
+        exact = true;
     }
+    if (!exact)
+        if (int rc = residual_to_host(A, m, n, k, W, H, scratch, &res, st)) return rc;
     *iters_done_host = done;
     *residual_host = res;
     return NMF_OK;
@@ -1197,6 +1234,7 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
     mon.normA2 = cv.take<double>(4097);
     mon.out = cv.take<double>((size_t)iters);
     mon.res = cv.take<double>((size_t)(m + 31) / 32 + 1);
+    mon.last_only = false;
     if (mirrored) NMF_HIP(launch_sumsq(A, m * n, mon.normA2 + 1, mon.normA2, st));
     if (int rc = dense_body(A, m, n, k, W, H, iters, eps, p, st, false, nullptr, nullptr, &mon)) return rc;
     NMF_HIP(hipMemcpyAsync(objective_host, mon.out, (size_t)iters * sizeof(double), hipMemcpyDeviceToHost, st));

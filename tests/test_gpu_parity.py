@@ -301,6 +301,13 @@ def test_mu_dense_tol_matches_algorithm_1_loop():
     assert done == done_r == 40
     assert abs(res - res_r) <= 1e-4 * res_r and res <= tol
     check(host(Wd), host(Hd), Wr, Hr, TOLN)
+    # checked after every iteration (Algorithm 1 as printed): the cheap expansion decides far from
+    # the tolerance, the exact evaluation near it; the stopping iteration is the oracle's
+    want, _, _ = oracle_trajectory(A, W, H, 12)
+    tol1 = 0.5 * (want[8] + want[9])
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_dense_tol(dev(A), 256, 192, 4, Wd, Hd, 1000, EPS, tol1, 1)
+    assert done == 10 and abs(res - want[9]) <= 1e-4 * want[9]
     # cap reached / tolerance already met
     Wd, Hd = dev(W), dev(H)
     done, res = nmf.nmf_mu_dense_tol(dev(A), 256, 192, 4, Wd, Hd, 7, EPS, 0.0, 5)
