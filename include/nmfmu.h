@@ -57,7 +57,7 @@ enum {
 };
 
 #define NMF_MU_MAX_K 64           /* ranks served by the fused kernels */
-#define NMF_MU_MAX_K_SLICED 1024  /* ranks served 32 factor columns at a time (see nmf_mu_dense) */
+#define NMF_MU_MAX_K_SLICED 1024  /* ranks served 64 factor columns at a time (see nmf_mu_dense) */
 
 /* Static, human-readable name of a status code. */
 const char *nmf_status_string(int status);
@@ -77,10 +77,10 @@ const char *nmf_last_error(void);
  * A H^T kernel on A.  Both give the same iteration; low-order bits differ.
  * Ranks NMF_MU_MAX_K < k <= NMF_MU_MAX_K_SLICED run the same iteration with every
  * product written as F^T X (a reduction over the rows of two row-major
- * matrices) and computed 32 factor columns of F at a time by the k <= 32 pass
+ * matrices) and computed 64 factor columns of F at a time by the k <= 64 pass
  * kernel: W^T A, W^T W, (W^T W) H, and the same three on the transposes A^T,
  * H^T, W^T for the W update, followed by the element-wise update.  A is read
- * ceil(k / 32) times per product; the workspace holds A^T, W^T, H^T and two
+ * ceil(k / 64) times per product; the workspace holds A^T, W^T, H^T and two
  * k x max(m, n) arrays (nmf_mu_workspace_bytes kind 5), else NMF_ENOMEM.
  */
 int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
@@ -276,17 +276,18 @@ int nmf_mu_release(void);
  * entries to a whole workgroup instead.  Asynchronous on `stream`. */
 int nmf_csr_partition(const int64_t *rowptr, int64_t m, int32_t nparts, int64_t *part, void *stream);
 
-/* The operand encoding of the W^T A pass for k <= 32.  The products of
+/* The operand encoding of the W^T A pass for k <= 64.  The products of
  * Algorithms 2-5 (W^T A, and A H^T as the same product on the transposes) are
  * formed on the bf16 matrix cores from exact pieces: a float x is cut into
  * x = h + m + l, h = x with its significand truncated to 8 bits, m = x - h
  * truncated likewise, l = x - h - m (each piece is a bf16, the sum is x bit
  * for bit for |x| >= 2^-110); all nine piece products of a term are
  * accumulated in fp32.  This call writes the pieces of X (rows x k, row-major,
- * device, k <= 32) as the kernels read them: for row group g = row / 8, piece
- * p (0: h, 1: m, 2: l) and factor c < 32, the eight bf16 of rows 8g .. 8g+7 at
- * planes[((g * 3 + p) * 32 + c) * 8 ..]; rows >= `rows` and factors >= k are
- * zero.  `planes`: device, ceil(rows / 8) * 768 uint16.  Asynchronous. */
+ * device, k <= 64) as the kernels read them, with KP = 32 factor slots per
+ * row group for k <= 32 and KP = 64 above: for row group g = row / 8, piece
+ * p (0: h, 1: m, 2: l) and factor c < KP, the eight bf16 of rows 8g .. 8g+7 at
+ * planes[((g * 3 + p) * KP + c) * 8 ..]; rows >= `rows` and factors >= k are
+ * zero.  `planes`: device, ceil(rows / 8) * 24 * KP uint16.  Asynchronous. */
 int nmf_split_planes(const float *X, int64_t rows, int32_t k, uint16_t *planes, void *stream);
 
 /* Column-ordered copy of a CSR matrix, the structure nmf_mu_csr derives for its

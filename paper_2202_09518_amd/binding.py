@@ -215,7 +215,8 @@ def nmf_csr_partition(rowptr, m, nparts, part, stream=None) -> None:
 
 
 def nmf_split_planes(X, rows, k, planes, stream=None) -> None:
-    """planes: int16 device tensor of ceil(rows / 8) * 768 elements (bf16 bit patterns)."""
+    """planes: int16 device tensor of ceil(rows / 8) * 24 * KP elements (bf16 bit patterns),
+    KP = 32 for k <= 32, else 64."""
     _check(lib().nmf_split_planes(_dev(X, torch.float32, "X"), rows, k, _dev(planes, torch.int16, "planes"),
                                   _stream(stream)))
 

@@ -320,27 +320,30 @@ int build_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, i
 
 // ---- rank-sliced engine (ranks above NMF_MU_MAX_K, and the host-resident-W pipeline) ----
 // Every product of the iteration is written as F^T X with F (rows x k) and X (rows x cols)
-// row-major, i.e. a reduction over the rows of both, and computed 32 factor columns at a
-// time by the k <= 32 pass kernel on the piece planes of that slice of F:
+// row-major, i.e. a reduction over the rows of both, and computed 64 factor columns at a
+// time by the k <= 64 pass kernel on the piece planes of that slice of F:
 //   W^T A, W^T W                      F = W,  X = A or W
 //   (W^T W) H                         F = W^T W (symmetric), X = H
 //   A H^T, H H^T, W (H H^T)           the same three on the transposes A^T, H^T, W^T
 // followed by the element-wise update.  X is read once per slice.
 struct Sliced {
     void *planes;     // planes_bytes(max rows of any F)
-    float *ppart;     // row-split partials of one slice: splits x 32 x max cols
+    float *ppart;     // row-split partials of one slice: splits x 64 x max cols
     size_t planes_cap, ppart_elems;
 };
 
 int sliced_ftx(const Sliced &e, const float *F, int64_t rows, int k, const float *X, int64_t cols,
                float *out, bool accumulate, hipStream_t st)
 {
-    const int splits = wta_splits(rows, cols, 32);
+    // factor columns per pass: the widest the pass kernels take from planes alone for this X
+    // (the slices of F are not contiguous, so the kernel that reads the factor itself is out)
+    const int kSlice = wta_planes_only_width(X, cols);
+    const int splits = wta_splits(rows, cols, kSlice);
     const int64_t rps = wta_rows_per_split(rows, splits);
-    if ((size_t)splits * 32 * (size_t)cols > e.ppart_elems || planes_bytes(rows) > e.planes_cap)
+    if ((size_t)splits * kSlice * (size_t)cols > e.ppart_elems || planes_bytes(rows) > e.planes_cap)
         return fail(NMF_EHIP, "internal: sliced scratch too small%s");
-    for (int c0 = 0; c0 < k; c0 += 32) {
-        const int kc = (k - c0 < 32) ? k - c0 : 32;
+    for (int c0 = 0; c0 < k; c0 += kSlice) {
+        const int kc = (k - c0 < kSlice) ? k - c0 : kSlice;
         NMF_HIP(launch_split_planes_slice(F, rows, k, c0, kc, e.planes, st));
         NMF_HIP(launch_wta_pass(X, rows, cols, kc, nullptr, e.planes, true, e.ppart, splits, rps, false, st));
         NMF_HIP(launch_sum_partials(e.ppart, splits, (int64_t)kc * cols, out + (int64_t)c0 * cols, st, accumulate));
@@ -348,12 +351,12 @@ int sliced_ftx(const Sliced &e, const float *F, int64_t rows, int k, const float
     return NMF_OK;
 }
 
-// Upper bound on splits x 32 x cols over every X with at most `cols` columns: the split count is
+// Upper bound on splits x 64 x cols over every X with at most `cols` columns: the split count is
 // at most 32 and at most 512 / slabs + 1 with cols <= 128 slabs.
 size_t sliced_ppart_elems(int64_t cols)
 {
     const int64_t a = 32 * cols, b = 65536 + cols;
-    return (size_t)32 * (size_t)(a < b ? a : b);
+    return (size_t)64 * (size_t)(a < b ? a : b);
 }
 
 // Resident run of rank k > NMF_MU_MAX_K.
@@ -1256,7 +1259,7 @@ int nmf_split_planes(const float *X, int64_t rows, int32_t k, uint16_t *planes, 
 {
     if (!X || !planes) return fail(NMF_EINVAL, "null pointer%s");
     if (rows < 1 || k < 1) return fail(NMF_EINVAL, "bad size%s");
-    if (!wta_uses_planes(k)) return fail(NMF_EUNSUPPORTED, "piece planes are used for k <= 32 only%s");
+    if (!wta_uses_planes(k)) return fail(NMF_EUNSUPPORTED, "piece planes are used for k <= 64 only%s");
     if (reinterpret_cast<uintptr_t>(planes) % 16) return fail(NMF_EINVAL, "planes must be 16-byte aligned%s");
     NMF_HIP(launch_split_planes(X, rows, k, planes, static_cast<hipStream_t>(stream)));
     return NMF_OK;

@@ -342,18 +342,18 @@ __global__ __launch_bounds__(64 * kWtaWaves, OCC) void wta_pass_kernel(const flo
 }
 
 // ---------------------------------------------------------------------------
-// Piece planes of kc <= 32 columns c0 .. c0 + kc - 1 of a factor X (rows x ld,
-// row-major), the A_op of the pass below:
-// planes[(g * 3 + p) * 32 + c] = the eight bf16 p-th pieces (p = 0: h, 1: m, 2: l)
-// of X[8 g .. 8 g + 7][c0 + c], c < 32; rows beyond `rows` and columns beyond kc are zero.
+// Piece planes of kc <= kp columns c0 .. c0 + kc - 1 of a factor X (rows x ld,
+// row-major), the A_op of the passes below; kp = 32 or 64 factor slots per row group:
+// planes[(g * 3 + p) * kp + c] = the eight bf16 p-th pieces (p = 0: h, 1: m, 2: l)
+// of X[8 g .. 8 g + 7][c0 + c], c < kp; rows beyond `rows` and columns beyond kc are zero.
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restrict__ X, int64_t rows,
-                                                           int64_t ld, int64_t c0, int k,
+                                                           int64_t ld, int64_t c0, int k, int kp,
                                                            u32x4 *__restrict__ planes)
 {
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t g = t >> 5;
-    const int c = (int)(t & 31);
+    const int64_t g = t / kp;
+    const int c = (int)(t % kp);
     if (g * 8 >= rows) return;
     u32x4 o[3];
 #pragma unroll
@@ -370,7 +370,7 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
         o[2][pr] = pack2(l[0], l[1]);
     }
 #pragma unroll
-    for (int pl = 0; pl < 3; ++pl) planes[(g * 3 + pl) * 32 + c] = o[pl];
+    for (int pl = 0; pl < 3; ++pl) planes[(g * 3 + pl) * kp + c] = o[pl];
 }
 
 // ---------------------------------------------------------------------------
@@ -597,6 +597,131 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
 }
 
 // ---------------------------------------------------------------------------
+// The pass for 32 < k <= 64 on exact pieces (aligned A, n % 4 == 0, 64 n < 2^31): as
+// wta_pass_split_buf_kernel, but a workgroup covers 64 columns (lane = 2 consecutive
+// columns, 8-byte loads) so that the two 32-factor accumulator tiles of a column tile
+// fit the registers of 2 waves per SIMD next to two steps of A and of the planes
+// (planes with 64 factor slots per row group).  The loads of the next step are kept
+// above the arithmetic of the current one by scheduling barriers.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_buf_kernel(
+    const float *__restrict__ A, const u32x4 *__restrict__ planes, float *__restrict__ ppart,
+    int64_t rows, int64_t n, int k, int64_t rps, int accumulate,
+    const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum)
+{
+    typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+    constexpr int NW = kWtaWaves, SW = 64, LD = SW + 4, KP = 64;
+    constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+    __shared__ float red[KP * LD];
+    if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int jj = lane & 31, half = lane >> 5;
+    const int64_t j0 = (int64_t)blockIdx.x * SW;
+    int64_t col = j0 + 2 * jj;
+    if (col >= n) col = 0;   // lanes past the edge read valid data that is never stored
+    const int64_t r0 = (int64_t)blockIdx.y * rps;
+    const int64_t r1 = (r0 + rps < rows) ? r0 + rps : rows;
+    const unsigned rowb = (unsigned)(n * 4);
+    const unsigned loff = (unsigned)(half * 8) * rowb + (unsigned)col * 4;
+    const unsigned poff = (unsigned)(half * 3 * KP + jj) * 16;
+    const int64_t ngroups = (rows + 7) >> 3;
+
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) acc[t][q] = f32x16{0};
+
+    struct Stage {
+        u32x2 a[8];
+        u32x4 wt[2][3];
+    };
+    auto load_stage = [&](Stage &s, int64_t ib) {
+        int64_t av = r1 - ib;                       // rows of this step inside the split
+        av = av < 0 ? 0 : (av > 16 ? 16 : av);
+        const int64_t g = ib >> 3;
+        int64_t ng = av ? ngroups - g : 0;          // 8-row groups of planes that exist
+        ng = ng < 0 ? 0 : (ng > 2 ? 2 : ng);
+        const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<float *>(A + (av ? ib : 0) * n), 0, (int)(av * rowb), kRsrcFlags);
+        const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<u32x4 *>(planes + (ng ? g : 0) * 3 * KP), 0, (int)(ng * 3 * KP * 16), kRsrcFlags);
+#pragma unroll
+        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b64(ra, loff + r * rowb, 0, 0);
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl)
+                s.wt[t][pl] = __builtin_amdgcn_raw_buffer_load_b128(rp, poff + (pl * KP + 32 * t) * 16, 0, 0);
+    };
+    auto compute = [&](const Stage &c) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            u32x4 at[3];
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                unsigned h0, m0, l0, h1, m1, l1;
+                split3(__uint_as_float(c.a[2 * pr][q]), h0, m0, l0);
+                split3(__uint_as_float(c.a[2 * pr + 1][q]), h1, m1, l1);
+                at[0][pr] = pack2(h0, h1);
+                at[1][pr] = pack2(m0, m1);
+                at[2][pr] = pack2(l0, l1);
+            }
+            constexpr int PW[9] = {2, 2, 1, 2, 1, 0, 1, 0, 0}, PA[9] = {2, 1, 2, 0, 1, 2, 0, 1, 0};   // smallest first
+#pragma unroll
+            for (int e = 0; e < 9; ++e)
+#pragma unroll
+                for (int t = 0; t < 2; ++t) acc[t][q] = mfma_bf16(c.wt[t][PW[e]], at[PA[e]], acc[t][q]);
+        }
+    };
+    const int64_t step = 16 * NW;
+    Stage s0, s1;
+    int64_t i = r0 + 16 * w;
+    load_stage(s0, i);
+    while (i < r1) {
+        load_stage(s1, i + step);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(s0);
+        __builtin_amdgcn_sched_barrier(0);
+        i += step;
+        if (i >= r1) break;
+        load_stage(s0, i + step);
+        __builtin_amdgcn_sched_barrier(0);
+        compute(s1);
+        __builtin_amdgcn_sched_barrier(0);
+        i += step;
+    }
+
+    for (int ww = 0; ww < NW; ++ww) {
+        if (w == ww) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int q = 0; q < 2; ++q)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const int idx = (32 * t + acc_row(v, half)) * LD + q * 32 + jj;
+                        if (ww == 0) red[idx] = acc[t][q][v];
+                        else red[idx] += acc[t][q][v];
+                    }
+        }
+        __syncthreads();
+    }
+    float *dst = ppart + (int64_t)blockIdx.y * k * n;
+    for (int e = tid; e < k * SW; e += 64 * NW) {
+        const int c = e / SW, x = e % SW;
+        const int64_t cj = j0 + x;
+        if (cj < n) {
+            float val = red[c * LD + (x & 1) * 32 + (x >> 1)];
+            float *p = dst + (int64_t)c * n + cj;
+            if (accumulate) val += *p;
+            *p = val;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // Factor update ("finisher").  For X (k x len), partials of its numerator and
 // the Gram matrix G of the other factor:
 //     X[c][j] <- X[c][j] * (sum_s part[s][c][j]) / (sum_d G[c][d] X[d][j] + eps).
@@ -748,9 +873,10 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                 if (ch * 64 + jj < len) Xt[(ch * 64 + jj) * k + c] = Ts[jj * LDT + c];
             }
         }
-        if (KP <= 32 && planes && tid < 256) {
+        constexpr int PKP = KP <= 32 ? 32 : 64;   // factor slots per row group of the planes
+        if (planes && tid < 8 * PKP) {
             // bf16 piece planes of the new X^T rows of this chunk (layout of split_planes_kernel)
-            const int gl = tid >> 5, c = tid & 31;
+            const int gl = tid / PKP, c = tid % PKP;
             const int64_t grow = ch * 8 + gl;
             if (grow * 8 < len) {
                 u32x4 o[3];
@@ -767,7 +893,7 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                     o[2][pr] = pack2(ll[0], ll[1]);
                 }
 #pragma unroll
-                for (int pl = 0; pl < 3; ++pl) planes[(grow * 3 + pl) * 32 + c] = o[pl];
+                for (int pl = 0; pl < 3; ++pl) planes[(grow * 3 + pl) * PKP + c] = o[pl];
             }
         }
         if (gout) {
@@ -1196,15 +1322,21 @@ static void wta_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, co
         hipLaunchKernelGGL((wta_pass_kernel<KT, U, OCC, false>), grid, block, 0, st, A, W, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
 }
 
-size_t planes_bytes(int64_t rows) { return (size_t)((rows + 7) / 8) * 3 * 32 * 16; }
+int wta_planes_only_width(const float *A, int64_t n)
+{
+    return (vec_ok(A, n) && n < ((int64_t)1 << 25)) ? 64 : 32;
+}
+
+size_t planes_bytes(int64_t rows) { return (size_t)((rows + 7) / 8) * 3 * 64 * 16; }   // 64 factor slots
 
 hipError_t launch_split_planes_slice(const float *X, int64_t rows, int64_t ld, int64_t c0, int kc,
                                      void *planes, hipStream_t st)
 {
-    if (kc < 1 || kc > 32) return hipErrorInvalidValue;
-    const int64_t threads = ((rows + 7) / 8) * 32;
+    if (kc < 1 || kc > 64) return hipErrorInvalidValue;
+    const int kp = kc <= 32 ? 32 : 64;
+    const int64_t threads = ((rows + 7) / 8) * kp;
     hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, X,
-                       rows, ld, c0, kc, static_cast<u32x4 *>(planes));
+                       rows, ld, c0, kc, kp, static_cast<u32x4 *>(planes));
     return hipGetLastError();
 }
 
@@ -1247,7 +1379,20 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
             hipLaunchKernelGGL((wta_pass_split_kernel<false>), grid, block, 0, st, A, pl, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
         break;
     }
-    case 2: wta_dispatch<2>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum); break;
+    case 2:
+        if (vec && planes && n < ((int64_t)1 << 25)) {
+            if (!planes_ready) {
+                hipError_t e = launch_split_planes(W, rows, k, planes, st);
+                if (e != hipSuccess) return e;
+            }
+            const dim3 grid64((unsigned)((n + 63) / 64), (unsigned)splits);
+            hipLaunchKernelGGL(wta_pass_split64_buf_kernel, grid64, dim3(64 * kWtaWaves), 0, st, A,
+                               static_cast<const u32x4 *>(planes), ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
+        } else {
+            if (!W) return hipErrorInvalidValue;   // this kernel reads the factor itself, not its planes
+            wta_dispatch<2>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
+        }
+        break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

@@ -45,10 +45,14 @@ hipError_t launch_gram_h(const float *X, int k, int64_t cols, float *G, float *g
                          unsigned *counters, hipStream_t st);
 // Ranks whose W^T A pass reads its factor as bf16 piece planes (planes_bytes(rows) bytes,
 // written by launch_split_planes from the rows x k factor) instead of the floats.
-inline bool wta_uses_planes(int k) { return k <= 32; }
+inline bool wta_uses_planes(int k) { return k <= 64; }
 size_t planes_bytes(int64_t rows);
+// Largest rank for which launch_wta_pass on this A (n columns) reads only the planes, never
+// the float factor W (which may then be null): 64 for aligned A with n % 4 == 0, else 32.
+int wta_planes_only_width(const float *A, int64_t n);
 hipError_t launch_split_planes(const float *X, int64_t rows, int k, void *planes, hipStream_t st);
-// The same for columns c0 .. c0 + kc - 1 (kc <= 32) of X with leading dimension ld.
+// The same for columns c0 .. c0 + kc - 1 (kc <= 64; 32 factor slots per row group up to kc = 32, else 64)
+// of X with leading dimension ld.
 hipError_t launch_split_planes_slice(const float *X, int64_t rows, int64_t ld, int64_t c0, int kc,
                                      void *planes, hipStream_t st);
 // ppart[s] (+)= W[r0_s:r1_s]^T A[r0_s:r1_s] for each row split s (k x n each).  `planes`:

@@ -234,7 +234,7 @@ def bf16_bits_to_f64(u16):
     return (u16.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
 
 
-@pytest.mark.parametrize("rows,k", [(1, 1), (8, 32), (13, 5), (1000, 32), (4099, 17)])
+@pytest.mark.parametrize("rows,k", [(1, 1), (8, 32), (13, 5), (1000, 32), (4099, 17), (100, 33), (515, 64)])
 def test_split_planes_encoding_is_exact(rows, k):
     """The three bf16 pieces of every factor entry add up to the entry bit for bit,
     each piece is the truncation the header states, the layout is the stated one
@@ -245,23 +245,24 @@ def test_split_planes_encoding_is_exact(rows, k):
     X[rows // 2, k // 2] = np.float32(1.0)          # one piece only
     X[rows - 1, k - 1] = np.float32(3.0e38)
     groups = (rows + 7) // 8
-    planes = torch.full((groups * 768,), -1, dtype=torch.int16, device="cuda")
+    KP = 32 if k <= 32 else 64
+    planes = torch.full((groups * 24 * KP,), -1, dtype=torch.int16, device="cuda")
     nmf.nmf_split_planes(dev(X), rows, k, planes)
     torch.cuda.synchronize()
-    P = planes.cpu().numpy().view(np.uint16).reshape(groups, 3, 32, 8)
+    P = planes.cpu().numpy().view(np.uint16).reshape(groups, 3, KP, 8)
     # host: truncation by masking the low 16 bits, exact float32 subtractions
-    Xp = np.zeros((groups * 8, 32), dtype=np.float32)
+    Xp = np.zeros((groups * 8, KP), dtype=np.float32)
     Xp[:rows, :k] = X
     h = (Xp.view(np.uint32) & np.uint32(0xffff0000)).view(np.float32)
     r1 = Xp - h
     m = (r1.view(np.uint32) & np.uint32(0xffff0000)).view(np.float32)
     l = r1 - m
     assert ((l.view(np.uint32) & np.uint32(0xffff)) == 0).all()      # the last piece is a bf16 already
-    want = np.stack([(x.view(np.uint32) >> 16).astype(np.uint16).reshape(groups, 8, 32).transpose(0, 2, 1)
+    want = np.stack([(x.view(np.uint32) >> 16).astype(np.uint16).reshape(groups, 8, KP).transpose(0, 2, 1)
                      for x in (h, m, l)], axis=1)
     np.testing.assert_array_equal(P, want)
     total = bf16_bits_to_f64(P[:, 0]) + bf16_bits_to_f64(P[:, 1]) + bf16_bits_to_f64(P[:, 2])
-    np.testing.assert_array_equal(total.transpose(0, 2, 1).reshape(groups * 8, 32), Xp.astype(np.float64))
+    np.testing.assert_array_equal(total.transpose(0, 2, 1).reshape(groups * 8, KP), Xp.astype(np.float64))
 
 
 # ---- objective and tolerance-driven run --------------------------------------------
