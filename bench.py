@@ -7,9 +7,9 @@ U[0.95, 1.05) noise, k = 32, W and H ~ U[0, 1).  One step = one MU iteration
 (H update then W update: W^T W, W^T A, H update, H H^T, A H^T with the fused W
 update), i.e. two full reads of A.
 
-Prints ONE JSON line on stdout.  Other workloads (--workload c1|c3|c4|c5) are
-there for the measurements quoted in the design doc; they print the same kind of
-line with their own unit.
+Prints ONE JSON line on stdout.  Other workloads (--workload c1|c3|c3ooc|c4|c5|oom1|ck) are
+there for the other measurements of this repository; they print the same kind
+of line with their own unit.
 """
 from __future__ import annotations
 
