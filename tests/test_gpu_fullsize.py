@@ -164,3 +164,39 @@ def test_rank_1024_resident_one_iteration():
     ew, eh = errs(W, H, Wr, Hr)
     say(f"rank 1024 resident, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
     assert max(ew, eh) < 1e-5
+
+
+def test_config5_one_copy_all_ranks_stacked_one_and_three_iterations():
+    """One perturbed copy with its 15 runs (k = 2..16) in one batched call, as bench.py --workload c5
+    issues them: the library stacks them 54 + 50 + 31 wide, so the 64-wide and the 32-wide pass
+    kernels both run at the full 16384 x 8192 shape.  Every run against its own oracle run."""
+    m, n = 16384, 8192
+    base = nmf_inputs.dense_planted(m, n, 8, seed=1005, device="cuda")
+    A = nmf_inputs.perturb(base, 3000)
+    Ah = A.cpu().numpy()
+    ks = list(range(2, 17))
+    for iters, tol in ((1, 1e-5), (3, 1e-4)):
+        Ws, Hs, W0s, H0s = [], [], [], []
+        for i, k in enumerate(ks):
+            W, H = nmf_inputs.init_factors(m, n, k, seed=2005 + i, device="cuda")
+            Ws.append(W); Hs.append(H); W0s.append(W.cpu().numpy()); H0s.append(H.cpu().numpy())
+        nmf.nmf_mu_dense_batched(len(ks), [A] * len(ks), m, n, ks, Ws, Hs, iters, EPS)
+        torch.cuda.synchronize()
+        worst = 0.0
+        for i, k in enumerate(ks):
+            Wr, Hr = orc.mu_dense(Ah, W0s[i], H0s[i], iters, EPSD)
+            worst = max(worst, *errs(Ws[i], Hs[i], Wr, Hr))
+        say(f"config 5 shape, 15 stacked runs, {iters} iteration(s): worst rel err {worst:.2e}")
+        assert worst < tol
+
+
+def test_rank_64_resident_config2_matrix_one_iteration():
+    m, n, k = 32768, 16384, 64
+    A = nmf_inputs.dense_planted(m, n, 32, seed=1002, device="cuda")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2002, device="cuda")
+    Ah, W0, H0 = A.cpu().numpy(), W.cpu().numpy(), H.cpu().numpy()
+    nmf.nmf_mu_dense(A, m, n, k, W, H, 1, EPS)
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 1, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    say(f"rank 64 on config 2's matrix, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 1e-5
