@@ -1120,7 +1120,7 @@ int residual_to_host(const float *A, int64_t m, int64_t n, int k, const float *W
     (void)blocks;
     return NMF_OK;
 }
-size_t residual_scratch_bytes(int64_t m) { return align_up(((size_t)(m + 31) / 32 + 1) * sizeof(double)); }
+size_t residual_scratch_bytes(int64_t m, int64_t n) { return align_up(((size_t)residual_partials(m, n) + 1) * sizeof(double)); }
 }  // namespace
 
 int nmf_residual_dense(const float *A, int64_t m, int64_t n, int32_t k, const float *W,
@@ -1130,10 +1130,10 @@ int nmf_residual_dense(const float *A, int64_t m, int64_t n, int32_t k, const fl
     if (!residual_host) return fail(NMF_EINVAL, "null pointer%s");
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
-    if (int rc = ensure_workspace(kAlign + residual_scratch_bytes(m), &ws)) return rc;
+    if (int rc = ensure_workspace(kAlign + residual_scratch_bytes(m, n), &ws)) return rc;
     Carve cv(ws);
     cv.take<unsigned>(64);   // the arrival counters at the head of the workspace stay untouched
-    double *scratch = cv.take<double>((size_t)(m + 31) / 32 + 1);
+    double *scratch = cv.take<double>((size_t)residual_partials(m, n) + 1);
     return residual_to_host(A, m, n, k, W, H, scratch, residual_host, static_cast<hipStream_t>(stream));
 }
 
@@ -1149,7 +1149,7 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     void *ws = nullptr;
     bool mirrored = false;
     // the residual scratch and the monitor's few doubles ride behind whichever dense plan fits
-    const size_t extra = residual_scratch_bytes(m) + align_up((size_t)kFinMaxBlocks * sizeof(double)) +
+    const size_t extra = residual_scratch_bytes(m, n) + align_up((size_t)kFinMaxBlocks * sizeof(double)) +
                          align_up(4097 * sizeof(double)) + kAlign;
     const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
     if ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK)) {
@@ -1161,7 +1161,7 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     ws = g.ws;
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
     Carve cv(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
-    double *scratch = cv.take<double>((size_t)(m + 31) / 32 + 1);
+    double *scratch = cv.take<double>((size_t)residual_partials(m, n) + 1);
     Monitor mon;
     mon.dpart = cv.take<double>(kFinMaxBlocks);
     mon.normA2 = cv.take<double>(4097);
@@ -1219,7 +1219,7 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g.mu);
     const size_t extra = align_up((size_t)kFinMaxBlocks * sizeof(double)) + align_up(4097 * sizeof(double)) +
-                         align_up((size_t)iters * sizeof(double)) + residual_scratch_bytes(m);
+                         align_up((size_t)iters * sizeof(double)) + residual_scratch_bytes(m, n);
     const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
     void *ws = nullptr;
     bool mirrored = false;
@@ -1236,7 +1236,7 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
     mon.dpart = cv.take<double>(kFinMaxBlocks);
     mon.normA2 = cv.take<double>(4097);
     mon.out = cv.take<double>((size_t)iters);
-    mon.res = cv.take<double>((size_t)(m + 31) / 32 + 1);
+    mon.res = cv.take<double>((size_t)residual_partials(m, n) + 1);
     mon.last_only = false;
     if (mirrored) NMF_HIP(launch_sumsq(A, m * n, mon.normA2 + 1, mon.normA2, st));
     if (int rc = dense_body(A, m, n, k, W, H, iters, eps, p, st, false, nullptr, nullptr, &mon)) return rc;

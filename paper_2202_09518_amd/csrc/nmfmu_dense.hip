@@ -1157,6 +1157,152 @@ __global__ __launch_bounds__(256) void residual_kernel(const float *__restrict__
     if (tid == 0) partial[blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
 }
 
+// ---------------------------------------------------------------------------
+// The same objective as a streaming pass for k = 16 or 32, 16-byte aligned A, W and H,
+// n % 4 == 0 and m % 32 == 0 (the launcher gives the rows left over to the general kernel):
+// the geometry and the exact-piece arithmetic of the W^T A pass, turned round: here the
+// 32 x 32 tile of an instruction is rows of A by columns of A and the reduction runs over the
+// factor index.  Workgroup = 4 waves on 256 consecutive columns and one row split; a wave
+// owns 64 of the columns and walks down all the rows of the split, a lane 2 consecutive
+// columns.  Once per wave its slab of H is cut into bf16 pieces (B_op: lane l holds factors
+// 8 (l / 32) .. + 7 of 16 for column l % 32), kept in registers for every row tile.  Per
+// 32-row tile a wave loads the rows of W (A_op: lane l holds 8 consecutive factors of row
+// l % 32), cuts them into pieces, forms the two 32 x 32 tiles of W H with 2 x 9 instructions
+// each, and subtracts them from the tile of A, loaded in the accumulator layout (lane l,
+// register v: row (v % 4) + 4 (l / 32) + 8 (v / 4), its 2 columns: 8-byte loads, 1 KiB
+// contiguous per row over the workgroup).  The next tile of A is requested before the
+// current tile's arithmetic and the next tile's rows of W once the current ones are cut.
+// One double per workgroup.  Measured on the 32768 x 16384, k = 32 case the matrix
+// instructions' time adds to the streaming time instead of hiding under it (six of the nine
+// products take 53 us less), which leaves the kernel at 4.4 TB/s.
+// ---------------------------------------------------------------------------
+template <int KSTEPS>
+__global__ __launch_bounds__(256, 2) void residual_stream_kernel(const float *__restrict__ A,
+                                                                 const float *__restrict__ W,
+                                                                 const float *__restrict__ H, int64_t m,
+                                                                 int64_t n, int64_t rps,
+                                                                 double *__restrict__ partial)
+{
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    constexpr int k = 16 * KSTEPS;
+    __shared__ double wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int jj = lane & 31, half = lane >> 5;
+    const int64_t jw = (int64_t)blockIdx.x * 256 + 64 * w;   // this wave's 64 columns
+    const int64_t col = jw + 2 * jj;
+    const bool colok = col < n;                       // n is even: both columns or none
+    const int64_t j0 = jw < n ? jw : 0;               // a wave wholly past column n fetches the first slab
+    const int64_t r0 = (int64_t)blockIdx.y * rps;     // rps % 32 == 0
+    const int64_t r1 = (r0 + rps < m) ? r0 + rps : m;
+
+    // B_op pieces of the slab of H: hp[s][q][piece]
+    u32x4 hp[KSTEPS][2][3];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s) {
+        f32x2 hv[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const int c = 16 * s + 8 * half + r;
+            const f32x2 t = *reinterpret_cast<const f32x2 *>(H + (colok ? (int64_t)c * n + col : 0));
+            hv[r].x = colok ? t.x : 0.f;
+            hv[r].y = colok ? t.y : 0.f;
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                unsigned h0, m0, l0, h1, m1, l1;
+                split3(hv[2 * pr][q], h0, m0, l0);
+                split3(hv[2 * pr + 1][q], h1, m1, l1);
+                hp[s][q][0][pr] = pack2(h0, h1);
+                hp[s][q][1][pr] = pack2(m0, m1);
+                hp[s][q][2][pr] = pack2(l0, l1);
+            }
+    }
+
+    // Requests only: nothing below reads a loaded value before the products of the previous
+    // tile are issued, so the loads stay in flight.  m % 32 == 0 and rps % 32 == 0: every tile
+    // is whole; a request past the split fetches tile 0 instead and is never used.
+    // this lane's row of W for tile i0: 8 consecutive factors per 16-factor step
+    f32x4 wv[KSTEPS][2];
+    auto load_w = [&](int64_t i0) {
+        const float *src = W + ((i0 < r1 ? i0 : 0) + jj) * k + 8 * half;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s) {
+            wv[s][0] = *reinterpret_cast<const f32x4 *>(src + 16 * s);
+            wv[s][1] = *reinterpret_cast<const f32x4 *>(src + 16 * s + 4);
+        }
+    };
+    // A in the accumulator layout: wave-uniform row address plus one 32-bit lane offset
+    // (4 n + 62 < 2^32); lanes past column n fetch the slab's first columns
+    typedef f32x2 ATile[16];
+    const unsigned lane_off = colok ? (unsigned)(4 * half) * (unsigned)n + 2u * jj : 0u;
+    auto load_a = [&](ATile &a, int64_t i0) {
+        const float *tp = A + (i0 < r1 ? i0 : 0) * n + j0;
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            a[v] = *reinterpret_cast<const f32x2 *>(tp + (int64_t)((v & 3) + 8 * (v >> 2)) * n + lane_off);
+    };
+
+    double total = 0.0;
+    // one tile, its A already requested: cut W, request the next tile's W, products, differences
+    auto tile = [&](const ATile &a, int64_t i0, bool valid) {
+        u32x4 wp[KSTEPS][3];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+            for (int pr = 0; pr < 4; ++pr) {
+                unsigned h0, m0, l0, h1, m1, l1;
+                split3(wv[s][pr >> 1][(2 * pr) & 3], h0, m0, l0);
+                split3(wv[s][pr >> 1][(2 * pr + 1) & 3], h1, m1, l1);
+                wp[s][0][pr] = pack2(h0, h1);
+                wp[s][1][pr] = pack2(m0, m1);
+                wp[s][2][pr] = pack2(l0, l1);
+            }
+        load_w(i0 + 32);
+        __builtin_amdgcn_sched_barrier(0);
+        f32x16 acc[2];
+        acc[0] = f32x16{0};
+        acc[1] = f32x16{0};
+        constexpr int PW[9] = {2, 2, 1, 2, 1, 0, 1, 0, 0}, PH[9] = {2, 1, 2, 0, 1, 2, 0, 1, 0};   // smallest first
+#pragma unroll
+        for (int e = 0; e < 9; ++e)
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) acc[q] = mfma_bf16(wp[s][PW[e]], hp[s][q][PH[e]], acc[q]);
+        __builtin_amdgcn_sched_barrier(0);
+        float local = 0.f;      // 32 terms per lane in fp32, double across tiles
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const float d0 = a[v].x - acc[0][v], d1 = a[v].y - acc[1][v];
+            local += d0 * d0;
+            local += d1 * d1;
+        }
+        total += valid ? (double)local : 0.0;
+    };
+    // two tiles per trip; the second may lie past the split: it is then tile 0 again, and
+    // its sum is dropped
+    ATile a0, a1;
+    int64_t i = r0;
+    load_w(i);
+    load_a(a0, i);
+    for (; i < r1; i += 64) {
+        load_a(a1, i + 32);
+        __builtin_amdgcn_sched_barrier(0);
+        tile(a0, i, true);
+        load_a(a0, i + 64);
+        __builtin_amdgcn_sched_barrier(0);
+        tile(a1, i + 32, i + 32 < r1);
+    }
+    if (!colok) total = 0.0;   // such lanes subtracted a zero product from columns of other lanes
+    for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off);
+    if (lane == 0) wsum[w] = total;
+    __syncthreads();
+    if (tid == 0) partial[(int64_t)blockIdx.y * gridDim.x + blockIdx.x] = (wsum[0] + wsum[1]) + (wsum[2] + wsum[3]);
+}
+
 // out[0] = sqrt(sum of `count` partials), added in index order by one thread.
 __global__ void residual_finish_kernel(const double *__restrict__ partial, int64_t count, double *out)
 {
@@ -1463,9 +1609,47 @@ hipError_t launch_objective(const double *dpart, int nb, const float *GW, const 
     return hipGetLastError();
 }
 
+// Row splits of the streaming objective kernel: one resident set of workgroups, whole 32-row tiles.
+static int residual_splits(int64_t m, int64_t n)
+{
+    const int64_t slabs = (n + 255) / 256;
+    int64_t s = (512 + slabs - 1) / slabs;
+    const int64_t by_rows = (m + 31) / 32;
+    if (s > by_rows) s = by_rows;
+    if (s < 1) s = 1;
+    return (int)s;
+}
+
+int64_t residual_partials(int64_t m, int64_t n)
+{
+    const int64_t a = (m + 31) / 32, b = ((n + 255) / 256) * residual_splits(m & ~(int64_t)31, n) + 1;
+    return a > b ? a : b;
+}
+
 hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const float *W,
                            const float *H, double *partial, double *out, hipStream_t st)
 {
+    const int64_t m32 = m & ~(int64_t)31;
+    if (m32 > 0 && k <= 32 && k % 16 == 0 && vec_ok(A, n) && vec_ok(H, n) && vec_ok(W, k)) {
+        // whole 32-row tiles by the streaming kernel, the up to 31 rows left by one workgroup
+        // of the general one
+        const int splits = residual_splits(m32, n);
+        int64_t rps = (m32 + splits - 1) / splits;
+        rps = (rps + 31) & ~(int64_t)31;
+        const dim3 grid((unsigned)((n + 255) / 256), (unsigned)splits);
+        int64_t count = (int64_t)grid.x * grid.y;
+        if (k == 16)
+            hipLaunchKernelGGL(residual_stream_kernel<1>, grid, dim3(256), 0, st, A, W, H, m32, n, rps, partial);
+        else
+            hipLaunchKernelGGL(residual_stream_kernel<2>, grid, dim3(256), 0, st, A, W, H, m32, n, rps, partial);
+        if (m > m32) {
+            hipLaunchKernelGGL((residual_kernel<1, true>), dim3(1), dim3(256), 0, st, A + m32 * n, W + m32 * k, H,
+                               m - m32, n, k, partial + count);
+            ++count;
+        }
+        hipLaunchKernelGGL(residual_finish_kernel, dim3(1), dim3(64), 0, st, (const double *)partial, count, out);
+        return hipGetLastError();
+    }
     const int64_t blocks = (m + 31) / 32;
     const bool vec = vec_ok(A, n) && vec_ok(H, n);
     const dim3 grid((unsigned)blocks), block(256);

@@ -97,7 +97,8 @@ int gram_w_blocks(int64_t rows);
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
                            const float *GH, float *W, float eps, hipStream_t st);
 
-// out[0] = ||A - W H||_F; partial: ceil(m / 32) doubles of scratch.
+// out[0] = ||A - W H||_F; partial: residual_partials(m, n) doubles of scratch.
+int64_t residual_partials(int64_t m, int64_t n);
 hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const float *W,
                            const float *H, double *partial, double *out, hipStream_t st);
 

@@ -267,7 +267,10 @@ def test_split_planes_encoding_is_exact(rows, k):
 
 # ---- objective and tolerance-driven run --------------------------------------------
 
-@pytest.mark.parametrize("m,n,k", SHAPES + [(4096, 2048, 32)])
+# the last six take the streaming kernel: whole 32-row tiles (with up to 31 rows left to the
+# general one), ragged and single column slabs, both factor step counts, fewer tiles than waves
+@pytest.mark.parametrize("m,n,k", SHAPES + [(4096, 2048, 32), (1000, 520, 16), (31, 64, 32), (32, 4, 16),
+                                            (4128, 68, 16), (163, 8200, 32), (8192, 64, 32)])
 def test_residual_dense(m, n, k):
     A, W, H = case(m, n, k, 32)
     got = nmf.nmf_residual_dense(dev(A), m, n, k, dev(W), dev(H))
