@@ -148,8 +148,7 @@ struct DensePlan {
 
 size_t dense_bytes(int64_t m, int64_t n, int k, bool mirrored)
 {
-    // split counts shrink with k, so the count for rank 1 bounds every stack of rank <= k
-    const size_t p1 = (size_t)wta_splits(m, n, 1) * k * n, p2 = (size_t)wta_splits(n, m, 1) * k * m;
+    const size_t p1 = (size_t)wta_splits_bound(m, n, k) * k * n, p2 = (size_t)wta_splits_bound(n, m, k) * k * m;
     size_t b = common_bytes(k) + align_up(((mirrored && p2 > p1) ? p2 : p1) * sizeof(float)) +
                align_up(planes_bytes((mirrored && n > m) ? n : m));
     if (mirrored)
@@ -168,7 +167,7 @@ DensePlan carve_dense(void *ws, int64_t m, int64_t n, int k, bool mirrored)
     p.rps1 = wta_rows_per_split(m, p.s1);
     p.s2 = wta_splits(n, m, k);
     p.rps2 = wta_rows_per_split(n, p.s2);
-    const size_t p1 = (size_t)wta_splits(m, n, 1) * k * n, p2 = (size_t)wta_splits(n, m, 1) * k * m;
+    const size_t p1 = (size_t)wta_splits_bound(m, n, k) * k * n, p2 = (size_t)wta_splits_bound(n, m, k) * k * m;
     p.ppart = cv.take<float>((mirrored && p2 > p1) ? p2 : p1);
     p.planes = cv.take<char>(planes_bytes((mirrored && n > m) ? n : m));
     p.At = p.Wt = p.Ht = nullptr;
@@ -352,10 +351,11 @@ int sliced_ftx(const Sliced &e, const float *F, int64_t rows, int k, const float
 }
 
 // Upper bound on splits x 64 x cols over every X with at most `cols` columns: the split count is
-// at most 32 and at most 512 / slabs + 1 with cols <= 128 slabs.
+// at most 32 and at most 512 / slabs + 1 with cols <= 256 slabs (64-factor slices; 32-factor
+// slices have 128-column slabs and half the factors).
 size_t sliced_ppart_elems(int64_t cols)
 {
-    const int64_t a = 32 * cols, b = 65536 + cols;
+    const int64_t a = 32 * cols, b = 131072 + cols;
     return (size_t)64 * (size_t)(a < b ? a : b);
 }
 

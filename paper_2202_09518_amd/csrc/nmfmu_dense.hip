@@ -76,6 +76,56 @@ __device__ __forceinline__ unsigned pack2(unsigned even, unsigned odd)
 // Row of the 32 x 32 accumulator held in register v of a lane in half `half`.
 __device__ __forceinline__ int acc_row(int v, int half) { return (v & 3) + 4 * half + 8 * (v >> 2); }
 
+// Running totals of the piece passes.  The bf16 matrix instruction aligns its 16 products
+// and the accumulator on the largest exponent and drops what falls below its adder's
+// width without rounding, so an accumulator that has grown over thousands of rows loses
+// the low bits of every product it takes in, always downwards: measured on uniform data
+// the sum over 2048 rows comes out 1.7e-6 low, over 4096 rows 1.1e-5, while up to 512 rows
+// the loss is below 1e-7.  The pass kernels therefore keep a matrix accumulator for at most
+// kFlushSteps 16-row steps and then add it, with ordinary rounded fp32 adds, into a total
+// that the wave keeps in its own 16 KiB of LDS (64 accumulator registers x 64 lanes; no
+// other wave touches it, so no barrier).  Slot of register r of tile q for a lane: the
+// lane index is flipped by 8 q so that the epilogue, which walks columns 4 jj + q, reads
+// 32 different banks.
+constexpr int kFlushSteps = 32;
+constexpr int kTotFloats = 64 * 64;
+__device__ __forceinline__ int tot_slot(int q, int v, int lane) { return (q * 16 + v) * 64 + (lane ^ (8 * q)); }
+
+__device__ __forceinline__ void tot_clear(float *tot, int lane)
+{
+#pragma unroll
+    for (int r = 0; r < 64; ++r) tot[r * 64 + lane] = 0.f;
+}
+
+// tot += acc; acc = 0 (four column tiles of one 32-factor tile)
+__device__ __forceinline__ void tot_flush4(float *tot, f32x16 (&acc)[4], int lane)
+{
+    // a tile at a time: 16 reads in flight, then the adds, then the writes
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        float t[16];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t[v] = tot[tot_slot(q, v, lane)];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            tot[tot_slot(q, v, lane)] = t[v] + acc[q][v];
+            acc[q][v] = 0.f;
+        }
+    }
+}
+
+// Epilogue of the 128-column kernels: the four waves' totals of (factor c, column x of the
+// slab), added in wave order.
+__device__ __forceinline__ float tot_sum4(const float *tot, int c, int x)
+{
+    const int q = x & 3, jj = x >> 2, half = (c >> 2) & 1, v = (c & 3) | ((c >> 3) << 2);
+    const int idx = tot_slot(q, v, 32 * half + jj);
+    float val = tot[idx];
+#pragma unroll
+    for (int ww = 1; ww < kWtaWaves; ++ww) val += tot[ww * kTotFloats + idx];
+    return val;
+}
+
 // Four consecutive elements X[row][col .. col+3] of a row-major matrix with
 // `ncols` columns; elements outside the matrix (or the whole group, if !ok)
 // read as zero.  VEC needs a 16-byte aligned base and ncols % 4 == 0, col % 4 == 0.
@@ -391,10 +441,11 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_kernel(
     const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum)
 {
     constexpr int NW = kWtaWaves;
-    constexpr int LD = 132;
-    __shared__ float red[32 * LD];
+    __shared__ float tot[NW * kTotFloats];
     if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    float *mytot = tot + w * kTotFloats;
+    tot_clear(mytot, lane);
     const int jj = lane & 31, half = lane >> 5;
     const int64_t j0 = (int64_t)blockIdx.x * kWtaCols;
     const int64_t col = j0 + 4 * jj;
@@ -422,8 +473,13 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_kernel(
     const int64_t step = 16 * NW;
     Stage cur, nxt;
     int64_t i = r0 + 16 * w;
+    int steps = 0;
     load_stage(cur, i);
     for (; i < r1; i += step) {
+        if (++steps > kFlushSteps) {
+            tot_flush4(mytot, acc, lane);
+            steps = 1;
+        }
         load_stage(nxt, i + step);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
@@ -450,25 +506,14 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_kernel(
         cur = nxt;
     }
 
-    for (int ww = 0; ww < NW; ++ww) {
-        if (w == ww) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int idx = acc_row(v, half) * LD + q * 32 + jj;
-                    if (ww == 0) red[idx] = acc[q][v];
-                    else red[idx] += acc[q][v];
-                }
-        }
-        __syncthreads();
-    }
+    tot_flush4(mytot, acc, lane);
+    __syncthreads();
     float *dst = ppart + (int64_t)blockIdx.y * k * n;
     for (int e = tid; e < k * kWtaCols; e += 64 * NW) {
         const int c = e >> 7, x = e & 127;
         const int64_t cj = j0 + x;
         if (cj < n) {
-            float val = red[c * LD + (x & 3) * 32 + (x >> 2)];
+            float val = tot_sum4(tot, c, x);
             float *p = dst + (int64_t)c * n + cj;
             if (accumulate) val += *p;
             *p = val;
@@ -492,12 +537,13 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
     const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum)
 {
     constexpr int NW = kWtaWaves;
-    constexpr int LD = 132;
     constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
-    __shared__ float red[32 * LD];
+    __shared__ float tot[NW * kTotFloats];
     if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float *mytot = tot + w * kTotFloats;
+    tot_clear(mytot, lane);
     const int jj = lane & 31, half = lane >> 5;
     const int64_t j0 = (int64_t)blockIdx.x * kWtaCols;
     int64_t col = j0 + 4 * jj;
@@ -559,6 +605,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
     const int64_t step = 16 * NW;
     Stage s0, s1;
     int64_t i = r0 + 16 * w;
+    int pairs = 4 * w;   // the waves of a workgroup flush at different times
     load_stage(s0, i);
     while (i < r1) {
         load_stage(s1, i + step);
@@ -568,27 +615,20 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
         load_stage(s0, i + step);
         compute(s1);
         i += step;
+        if (++pairs == kFlushSteps / 2) {
+            tot_flush4(mytot, acc, lane);
+            pairs = 0;
+        }
     }
 
-    for (int ww = 0; ww < NW; ++ww) {
-        if (w == ww) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int idx = acc_row(v, half) * LD + q * 32 + jj;
-                    if (ww == 0) red[idx] = acc[q][v];
-                    else red[idx] += acc[q][v];
-                }
-        }
-        __syncthreads();
-    }
+    tot_flush4(mytot, acc, lane);
+    __syncthreads();
     float *dst = ppart + (int64_t)blockIdx.y * k * n;
     for (int e = tid; e < k * kWtaCols; e += 64 * NW) {
         const int c = e >> 7, x = e & 127;
         const int64_t cj = j0 + x;
         if (cj < n) {
-            float val = red[c * LD + (x & 3) * 32 + (x >> 2)];
+            float val = tot_sum4(tot, c, x);
             float *p = dst + (int64_t)c * n + cj;
             if (accumulate) val += *p;
             *p = val;
@@ -597,29 +637,40 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// The pass for 32 < k <= 64 on exact pieces (aligned A, n % 4 == 0, 64 n < 2^31): as
-// wta_pass_split_buf_kernel, but a workgroup covers 64 columns (lane = 2 consecutive
-// columns, 8-byte loads) so that the two 32-factor accumulator tiles of a column tile
-// fit the registers of 2 waves per SIMD next to two steps of A and of the planes
-// (planes with 64 factor slots per row group).  The loads of the next step are kept
-// above the arithmetic of the current one by scheduling barriers.
+// The pass for 32 < k <= 64 on exact pieces (aligned A, n % 4 == 0, 64 n < 2^31; planes with
+// 64 factor slots per row group).  The arithmetic of wta_pass_split_buf_kernel with two
+// 32-factor accumulator tiles per column tile, and another geometry: workgroup = 256
+// columns, wave w = columns 64 w .. 64 w + 63 of them (lane = 2 consecutive columns, 8-byte
+// loads), and all four waves walk the same 16-row steps of the split.  The piece planes of
+// a step (1.5 times the bytes of the step's A) are then fetched from L2 once per workgroup
+// and hit the vector cache for the other three waves, no sum across waves is needed, and
+// each wave stores its own 64 x 64 result: register v of tile (t, q) is factor
+// 32 t + row(v), column 2 jj + q, so (q = 0, q = 1) pair up to 8-byte stores, 256
+// contiguous bytes per row.  Loads run two steps ahead of the arithmetic (three register
+// stages), held there by scheduling barriers.  Measured on 32768 x 16384, k = 64: 490 us
+// against 531 us for waves interleaved down the rows of one 64-column slab; the matrix
+// pipe is busy 70 % of the cycles at the 1.7 GHz the chip sustains under this load.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_buf_kernel(
+__global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kernel(
     const float *__restrict__ A, const u32x4 *__restrict__ planes, float *__restrict__ ppart,
     int64_t rows, int64_t n, int k, int64_t rps, int accumulate,
     const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum)
 {
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
-    constexpr int NW = kWtaWaves, SW = 64, LD = SW + 4, KP = 64;
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    constexpr int KP = 64;
     constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
-    __shared__ float red[KP * LD];
+    __shared__ float tot[kWtaWaves * kTotFloats];
     if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    float *mytot = tot + w * kTotFloats;   // register (t, q, v) of this lane at ((2 t + q) * 16 + v) * 64 + lane
+    tot_clear(mytot, lane);
     const int jj = lane & 31, half = lane >> 5;
-    const int64_t j0 = (int64_t)blockIdx.x * SW;
-    int64_t col = j0 + 2 * jj;
-    if (col >= n) col = 0;   // lanes past the edge read valid data that is never stored
+    const int64_t jw = (int64_t)blockIdx.x * 256 + 64 * w;
+    if (jw >= n) return;     // no barrier below: a wave wholly past the edge has nothing to do
+    const int64_t colr = jw + 2 * jj;
+    const int64_t col = colr < n ? colr : 0;   // lanes past the edge read valid data that is never stored
     const int64_t r0 = (int64_t)blockIdx.y * rps;
     const int64_t r1 = (r0 + rps < rows) ? r0 + rps : rows;
     const unsigned rowb = (unsigned)(n * 4);
@@ -675,49 +726,66 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_buf_kernel
                 for (int t = 0; t < 2; ++t) acc[t][q] = mfma_bf16(c.wt[t][PW[e]], at[PA[e]], acc[t][q]);
         }
     };
-    const int64_t step = 16 * NW;
-    Stage s0, s1;
-    int64_t i = r0 + 16 * w;
-    load_stage(s0, i);
-    while (i < r1) {
-        load_stage(s1, i + step);
+    // three steps per trip, loads two steps ahead; a step past the split loads nothing (zero
+    // extent) and is skipped
+    auto flush = [&]() {
+        // a tile at a time: 16 reads in flight, then the adds, then the writes
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                float old[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) old[v] = mytot[((2 * t + q) * 16 + v) * 64 + lane];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {
+                    mytot[((2 * t + q) * 16 + v) * 64 + lane] = old[v] + acc[t][q][v];
+                    acc[t][q][v] = 0.f;
+                }
+            }
+    };
+    Stage s0, s1, s2;
+    int trips = 2 * w;   // the waves of a workgroup flush at different times
+    load_stage(s0, r0);
+    load_stage(s1, r0 + 16);
+    for (int64_t i = r0; i < r1; i += 48) {
+        if (++trips > kFlushSteps / 3) {
+            flush();
+            trips = 1;
+        }
+        load_stage(s2, i + 32);
         __builtin_amdgcn_sched_barrier(0);
         compute(s0);
         __builtin_amdgcn_sched_barrier(0);
-        i += step;
-        if (i >= r1) break;
-        load_stage(s0, i + step);
+        load_stage(s0, i + 48);
         __builtin_amdgcn_sched_barrier(0);
-        compute(s1);
+        if (i + 16 < r1) compute(s1);
         __builtin_amdgcn_sched_barrier(0);
-        i += step;
+        load_stage(s1, i + 64);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i + 32 < r1) compute(s2);
+        __builtin_amdgcn_sched_barrier(0);
     }
 
-    for (int ww = 0; ww < NW; ++ww) {
-        if (w == ww) {
+    if (colr < n) {
+        float *dst = ppart + (int64_t)blockIdx.y * k * n + colr;
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
+        for (int t = 0; t < 2; ++t)
 #pragma unroll
-                for (int q = 0; q < 2; ++q)
-#pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        const int idx = (32 * t + acc_row(v, half)) * LD + q * 32 + jj;
-                        if (ww == 0) red[idx] = acc[t][q][v];
-                        else red[idx] += acc[t][q][v];
+            for (int v = 0; v < 16; ++v) {
+                const int c = 32 * t + acc_row(v, half);
+                if (c < k) {
+                    f32x2 *p = reinterpret_cast<f32x2 *>(dst + (int64_t)c * n);
+                    f32x2 val = {mytot[((2 * t) * 16 + v) * 64 + lane] + acc[t][0][v],
+                                 mytot[((2 * t + 1) * 16 + v) * 64 + lane] + acc[t][1][v]};
+                    if (accumulate) {
+                        const f32x2 old = *p;
+                        val.x += old.x;
+                        val.y += old.y;
                     }
-        }
-        __syncthreads();
-    }
-    float *dst = ppart + (int64_t)blockIdx.y * k * n;
-    for (int e = tid; e < k * SW; e += 64 * NW) {
-        const int c = e / SW, x = e % SW;
-        const int64_t cj = j0 + x;
-        if (cj < n) {
-            float val = red[c * LD + (x & 1) * 32 + (x >> 1)];
-            float *p = dst + (int64_t)c * n + cj;
-            if (accumulate) val += *p;
-            *p = val;
-        }
+                    *p = val;
+                }
+            }
     }
 }
 
@@ -1397,9 +1465,10 @@ int wta_splits(int64_t rows, int64_t n, int k)
 {
     // Enough workgroups to fill the chip once at the kernels' occupancy (2 groups per
     // compute unit), but long row ranges per group: every split costs a k x n partial
-    // result written and read again.
-    (void)k;
-    const int64_t slabs = (n + kWtaCols - 1) / kWtaCols;
+    // result written and read again.  A workgroup covers 128 columns up to 32 factors and
+    // 256 above.
+    const int64_t width = k > 32 ? 256 : kWtaCols;
+    const int64_t slabs = (n + width - 1) / width;
     const int64_t target = 512;
     int64_t s = (target + slabs - 1) / slabs;
     const int64_t max_by_rows = (rows + 255) / 256;   // at least 256 rows per split
@@ -1407,6 +1476,13 @@ int wta_splits(int64_t rows, int64_t n, int k)
     if (s > 32) s = 32;
     if (s < 1) s = 1;
     return (int)s;
+}
+
+int wta_splits_bound(int64_t rows, int64_t n, int k)
+{
+    // within a column width the count shrinks as slabs grow and does not depend on k
+    const int a = wta_splits(rows, n, 1), b = k > 32 ? wta_splits(rows, n, 64) : a;
+    return a > b ? a : b;
 }
 
 int64_t wta_rows_per_split(int64_t rows, int splits)
@@ -1531,8 +1607,8 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
                 hipError_t e = launch_split_planes(W, rows, k, planes, st);
                 if (e != hipSuccess) return e;
             }
-            const dim3 grid64((unsigned)((n + 63) / 64), (unsigned)splits);
-            hipLaunchKernelGGL(wta_pass_split64_buf_kernel, grid64, dim3(64 * kWtaWaves), 0, st, A,
+            const dim3 grid256((unsigned)((n + 255) / 256), (unsigned)splits);
+            hipLaunchKernelGGL(wta_pass_split64_wide_kernel, grid256, dim3(64 * kWtaWaves), 0, st, A,
                                static_cast<const u32x4 *>(planes), ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
         } else {
             if (!W) return hipErrorInvalidValue;   // this kernel reads the factor itself, not its planes

@@ -30,6 +30,8 @@ struct BlockMap {
 
 // Row split of the W^T A pass: number of partial k x n results, rows in each.
 int wta_splits(int64_t rows, int64_t n, int k);
+// Largest split count of any rank up to k on these dimensions (workspace sizing).
+int wta_splits_bound(int64_t rows, int64_t n, int k);
 int64_t wta_rows_per_split(int64_t rows, int splits);
 
 // ---- kernel launchers (all asynchronous on `st`; return hipGetLastError) ----

@@ -62,6 +62,25 @@ def test_wta_dense(m, n, k):
     assert rel(host(P), orc.wta_dense(A, W)) < TOL1
 
 
+# Few columns and many rows: a workgroup of the pass then walks 8192 rows.  The bf16 matrix
+# instruction drops the bits of a product that fall below its accumulator's width without
+# rounding, so a matrix accumulator kept over that many rows comes out low (1e-5 relative
+# at 4096 rows on this data); the kernels bound its run and add the pieces up in rounded
+# fp32.  n = 514 takes the kernels for unaligned rows (plain loads; fp32 instruction above
+# 32 factors).
+@pytest.mark.parametrize("m,n,k", [(262144, 512, 32), (262144, 512, 64), (262144, 514, 32), (262144, 514, 64),
+                                   (100000, 1024, 48)])
+def test_wta_dense_long_sums_keep_fp32_accuracy(m, n, k):
+    A = nmf_inputs.uniform((m, n), 77).numpy()
+    W = nmf_inputs.uniform((m, k), 78).numpy()
+    P = torch.empty((k, n), device="cuda")
+    nmf.nmf_wta_dense(dev(A), m, n, k, dev(W), P)
+    want = orc.wta_dense(A, W)
+    got = host(P).astype(np.float64)
+    assert rel(got, want) < 3e-7
+    assert abs(np.mean((got - want) / want)) < 1.5e-7
+
+
 @pytest.mark.parametrize("n,k", [(5, 1), (131, 17), (1027, 33), (4100, 5), (20000, 32), (9999, 64)])
 def test_h_update_and_gram_h(n, k):
     r = np.random.default_rng(n + k)
