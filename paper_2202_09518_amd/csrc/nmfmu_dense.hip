@@ -747,6 +747,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kerne
     Stage s0, s1, s2;
     int trips = 2 * w;   // the waves of a workgroup flush at different times
     load_stage(s0, r0);
+    __builtin_amdgcn_sched_barrier(0);   // issue order = age order, also here: the waits in the loop count loads in flight
     load_stage(s1, r0 + 16);
     for (int64_t i = r0; i < r1; i += 48) {
         if (++trips > kFlushSteps / 3) {
