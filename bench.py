@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # HBM bytes per launch of the streaming pass kernel on the default workload, from the
 # FETCH_SIZE / WRITE_SIZE counters in profiles/dense_c2_hbm_traffic_pmc.txt (scaled by the
 # plain-copy calibration stated there); only reported when that workload is the one timed.
-C2_PASS_TRAFFIC_BYTES = (1070666.1 * 2.0 + 8208.6) * 1024.0
+C2_PASS_TRAFFIC_BYTES = (1070017.4 * 2.0 + 8208.6) * 1024.0
 EPS = 1e-16
 
 
