@@ -1707,7 +1707,8 @@ hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const fl
                            const float *H, double *partial, double *out, hipStream_t st)
 {
     const int64_t m32 = m & ~(int64_t)31;
-    if (m32 > 0 && k <= 32 && k % 16 == 0 && vec_ok(A, n) && vec_ok(H, n) && vec_ok(W, k)) {
+    // the streaming kernel adds a 32-bit lane offset of up to 4 n + 62 floats to a row address
+    if (m32 > 0 && k <= 32 && k % 16 == 0 && n < ((int64_t)1 << 29) && vec_ok(A, n) && vec_ok(H, n) && vec_ok(W, k)) {
         // whole 32-row tiles by the streaming kernel, the up to 31 rows left by one workgroup
         // of the general one
         const int splits = residual_splits(m32, n);

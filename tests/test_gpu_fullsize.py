@@ -200,3 +200,25 @@ def test_rank_64_resident_config2_matrix_one_iteration():
     ew, eh = errs(W, H, Wr, Hr)
     say(f"rank 64 on config 2's matrix, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
     assert max(ew, eh) < 1e-5
+
+
+@pytest.mark.parametrize("m,k", [(32, 16), (16, 40)])
+def test_more_than_2_to_25_columns(m, k):
+    """Past 2^25 columns a 16-row step of A no longer fits a buffer descriptor's 32-bit
+    extent: the pass over A takes the kernels with plain 64-bit addressing, the pass over
+    the transpose walks 2^25 rows per column slab, and the factor update sees 2^25 columns."""
+    n = (1 << 25) + 64
+    A = nmf_inputs.uniform((m, n), 1025, device="cuda")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2025, device="cuda")
+    Ah, W0, H0 = A.cpu().numpy(), W.cpu().numpy(), H.cpu().numpy()
+    P = torch.empty((k, n), device="cuda")
+    nmf.nmf_wta_dense(A, m, n, k, W, P)
+    ep = orc.rel_fro(P.cpu().numpy(), orc.wta_dense(Ah, W0))
+    del P
+    got = nmf.nmf_residual_dense(A, m, n, k, W, H)
+    want = orc.residual_dense(Ah, W0, H0)
+    nmf.nmf_mu_dense(A, m, n, k, W, H, 1, EPS)
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 1, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    say(f"{m} x 2^25+64, k = {k}: rel err W^T A {ep:.2e}, objective {abs(got - want) / want:.2e}, 1 iteration W {ew:.2e} H {eh:.2e}")
+    assert ep < 1e-5 and abs(got - want) <= 1e-5 * want and max(ew, eh) < 1e-5
