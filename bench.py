@@ -154,6 +154,17 @@ def bench_c3(args, torch, nmf, nmf_inputs):
     nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, args.steps, EPS)
     t1 = sync_time(torch)
     ms_step = (t1 - t0) * 1e3 / args.steps
+    # the same iterations with the objective of every iteration reported
+    # (not part of the timed step): two calls of the same length, one plain, one monitored, so that
+    # the set-up of a call, which both pay, drops out of the difference
+    mon_iters = min(args.steps, 20)
+    t2 = sync_time(torch)
+    nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, mon_iters, EPS)
+    t3 = sync_time(torch)
+    obj = nmf.nmf_mu_csr_monitor(rowptr, colidx, vals, m, n, nnz, k, W, H, mon_iters, EPS)
+    t4 = sync_time(torch)
+    mon_extra_ms = ((t4 - t3) - (t3 - t2)) * 1e3 / mon_iters
+    log(f"[bench] c3 monitored: {mon_extra_ms:.2f} ms more per iteration than the plain run, objective {obj[-1]:.6g}")
     bytes_a = 2 * (8 * nnz + 8 * (m + 1))       # both passes read values, column indices, row pointers
     gbs = bytes_a / (ms_step * 1e-3) / 1e9
     gather = 2 * nnz * k * 4 + bytes_a
@@ -166,7 +177,9 @@ def bench_c3(args, torch, nmf, nmf_inputs):
             # (the tables, 128 MiB and 512 MiB here, do not fit the 4 MiB of L2 an XCD has)
             "roofline": {"bound": "hbm", "kernel": "aht_csr_kernel", "achieved": gather / (ms_step * 1e-3) / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gather / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": None, "algorithmic_bytes_per_iteration": gather}}
+                         "traffic": None, "algorithmic_bytes_per_iteration": gather},
+            "objective": {"residual_fro": obj[-1], "iterations": mon_iters,
+                          "ms_more_per_monitored_iteration": mon_extra_ms}}
 
 
 def bench_c3ooc(args, torch, nmf, nmf_inputs):

@@ -164,6 +164,26 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                float *W, float *H, int32_t iters, float eps, void *stream);
 
 /*
+ * nmf_mu_csr with the objective ||A - W H||_F reported after every iteration
+ * (Algorithm 1 evaluates it every iteration; for a sparse A the norm runs over
+ * all m n entries, zeros included).  It is taken from the expansion
+ * ||A||^2 - 2 <A H^T, W> + <H H^T, W^T W>, the only form that does not touch the
+ * m n entries of W H: <A H^T, W> is summed in double inside the W update from the
+ * gathered row sums against the new W, H H^T is the matrix the update used,
+ * W^T W of the new W costs one more read of W per iteration, ||A||^2 (sum of the
+ * squared stored values; repeated (row, column) pairs would have to be added
+ * first, so the value assumes there are none) once per call.  Absolute error
+ * about 2e-7 ||A||^2 / f as for nmf_mu_dense_monitor.  objective_host: HOST
+ * memory, iters doubles.  Blocking.  W, H as nmf_mu_csr (bit-identical result).
+ * The workspace is nmf_mu_workspace_bytes(kind 1) plus 8 (iters + 8449) bytes,
+ * rounded up to 256-byte pieces.
+ */
+int nmf_mu_csr_monitor(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                       int64_t m, int64_t n, int64_t nnz, int32_t k,
+                       float *W, float *H, int32_t iters, float eps,
+                       double *objective_host, void *stream);
+
+/*
  * Out-of-memory dense MU: A stays in host memory and is streamed to the device
  * in batches of `batch_rows` rows (co-linear batching, Algorithm 5; W and H
  * stay resident on the device).  Each sweep uploads A once: a batch first gets

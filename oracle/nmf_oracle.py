@@ -236,6 +236,21 @@ def residual_dense(A, W, H) -> float:
     return float(_load().oracle_residual_dense(_p(A), m, n, W.shape[1], _p(W), _p(H)))
 
 
+def residual_csr(rowptr, colidx, vals, m, n, W, H) -> float:
+    """||A - W H||_F over all m n entries for a CSR matrix without repeated
+    (row, column) pairs, without forming W H: the square is
+    ||A||^2 - 2 <A H^T, W> + <W^T W, H H^T> (expand the norm of section 2.1 and use
+    <A, W H> = trace(A^T W H) = <A H^T, W>, <W H, W H> = trace(H^T W^T W H)
+    = <W^T W, H H^T>).  All in double, from the oracle's own products."""
+    W = _f64(W)
+    H = _f64(H)
+    v = np.asarray(vals, dtype=np.float64)
+    a2 = float(np.dot(v, v))
+    cross = float(np.sum(aht_csr(rowptr, colidx, vals, H) * W))
+    gg = float(np.sum(gram_w(W) * gram_h(H)))
+    return float(np.sqrt(max(a2 - 2.0 * cross + gg, 0.0)))
+
+
 def mu_dense_tol(A, W0, H0, max_iters, eps, tol, check_every=1):
     """Algorithm 1's loop: iterate (H then W) until ||A - W H||_F <= tol or
     max_iters iterations have run; the objective is looked at before the first

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_csr_monitor", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_csr_partition", "nmf_split_planes", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -54,6 +54,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_residual_dense.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
     L.nmf_mu_dense_tol.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
     L.nmf_mu_csr.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp]
+    L.nmf_mu_csr_monitor.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_mu_ooc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
     L.nmf_mu_dense_monitor.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_mu_csr_ooc.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
@@ -143,6 +144,16 @@ def nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, stream=None
                             _dev(vals, torch.float32, "vals"), m, n, nnz, k,
                             _dev(W, torch.float32, "W"), _dev(H, torch.float32, "H"),
                             iters, eps, _stream(stream)))
+
+
+def nmf_mu_csr_monitor(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, stream=None):
+    """Runs `iters` iterations on a CSR matrix; returns the objective after each (list of floats, blocking)."""
+    out = (ctypes.c_double * max(iters, 1))()
+    _check(lib().nmf_mu_csr_monitor(_dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                    _dev(vals, torch.float32, "vals"), m, n, nnz, k,
+                                    _dev(W, torch.float32, "W"), _dev(H, torch.float32, "H"),
+                                    iters, eps, out, _stream(stream)))
+    return list(out)[:iters]
 
 
 def nmf_mu_ooc(A_host, m, n, k, W, H, iters, eps, batch_rows, device_budget_bytes, stream=None) -> None:

@@ -917,9 +917,18 @@ int nmf_mu_ooc_hostw(const float *A_host, float *W_host, int64_t m, int64_t n, i
                           static_cast<hipStream_t>(stream), device_bytes_host);
 }
 
-int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
-               int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t iters, float eps,
-               void *stream)
+// Bytes behind csr_bytes() that a monitored sparse run needs: the W update's by-products,
+// ||A||^2 with its scratch, one objective value per iteration.
+size_t csr_monitor_bytes(int iters)
+{
+    return align_up((size_t)kCsrDparts * sizeof(double)) + align_up(4097 * sizeof(double)) +
+           align_up((size_t)iters * sizeof(double));
+}
+
+// Resident sparse run; objective_host (iters doubles) == nullptr: no monitoring.
+static int csr_run(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
+                   int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t iters, float eps,
+                   double *objective_host, void *stream)
 {
     if (!rowptr) return fail(NMF_EINVAL, "null pointer%s");
     if (nnz < 0) return fail(NMF_EINVAL, "nnz must be >= 0%s");
@@ -931,7 +940,8 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
     if (nnz >= ((int64_t)1 << 31) || m >= ((int64_t)1 << 31))
         return fail(NMF_EUNSUPPORTED, "CSR path needs nnz < 2^31 and m < 2^31%s");
     void *ws = nullptr;
-    if (int rc = ensure_workspace(csr_bytes(n, nnz, k), &ws)) return rc;
+    if (int rc = ensure_workspace(csr_bytes(n, nnz, k) + (objective_host ? csr_monitor_bytes(iters) : 0), &ws))
+        return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
     float *Ht = cv.take<float>((size_t)n * k);
@@ -943,6 +953,14 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
     int32_t *long_r = cv.take<int32_t>((size_t)(nnz / kLongRow + 2));
     int32_t *long_c = cv.take<int32_t>((size_t)(nnz / kLongRow + 2));
     unsigned *long_n = cv.take<unsigned>(64);      // [0] rows of A, [1] columns of A
+    double *dpart = nullptr, *normA2 = nullptr, *obj = nullptr;
+    if (objective_host) {
+        dpart = cv.take<double>(kCsrDparts);
+        normA2 = cv.take<double>(4097);
+        obj = cv.take<double>((size_t)iters);
+        if (nnz > 0) NMF_HIP(launch_sumsq(vals, nnz, normA2 + 1, normA2, st));
+        else NMF_HIP(hipMemsetAsync(normA2, 0, sizeof(double), st));
+    }
 
     if (int rc = build_csc(rowptr, colidx, vals, m, n, nnz, colptr, rowidx, cvals, st)) return rc;
 
@@ -957,10 +975,37 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, 
         NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
         NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, W, c.gw, Ht, eps, st));   // H update on H^T
         NMF_HIP(launch_gram_w_wide(Ht, n, k, c.gh, c.ghp, st));
-        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st));        // W update
+        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st, false,
+                               dpart));                                                                       // W update
+        if (dpart) {
+            // ||A - W H||_F from what the W update leaves behind: <A H^T, W>, H H^T, and W^T W of the
+            // new W (computed here; the next iteration computes the same matrix again for its H update)
+            NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
+            NMF_HIP(launch_objective(dpart, kCsrDparts, c.gw, c.gh, k, normA2, obj + it, st));
+        }
     }
     NMF_HIP(launch_transpose(Ht, n, k, H, st));
+    if (dpart) {
+        NMF_HIP(hipMemcpyAsync(objective_host, obj, (size_t)iters * sizeof(double), hipMemcpyDeviceToHost, st));
+        NMF_HIP(hipStreamSynchronize(st));
+    }
     return NMF_OK;
+}
+
+int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
+               int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t iters, float eps,
+               void *stream)
+{
+    return csr_run(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, nullptr, stream);
+}
+
+int nmf_mu_csr_monitor(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
+                       int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t iters, float eps,
+                       double *objective_host, void *stream)
+{
+    if (!objective_host) return fail(NMF_EINVAL, "null pointer%s");
+    if (iters > (1 << 20)) return fail(NMF_EINVAL, "monitored run: iters <= 2^20%s");
+    return csr_run(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, objective_host, stream);
 }
 
 // Out-of-memory CSR: row batches of about batch_nnz stored entries each, streamed from host

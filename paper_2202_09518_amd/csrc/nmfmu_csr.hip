@@ -139,6 +139,9 @@ __device__ __forceinline__ float gather_chunk(const int32_t *__restrict__ colidx
 // Wavefront gw works on rows [part[gw], part[gw + 1]), 64 / LPR rows at a time.
 // accumulate != 0: no update; the gathered sums are added to W instead (the
 // numerator of an update collected over several row batches of the matrix; GH unused).
+// dpart (updating launch only): dpart[blockIdx.x] = sum over this block's rows of gathered
+// sum x new value in double, i.e. its share of <A H^T, W_new> for the objective
+// ||A||^2 - 2 <A H^T, W> + <H H^T, W^T W>; lanes by butterfly, then the 4 waves in order.
 // ---------------------------------------------------------------------------
 template <int LPR>
 __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict__ rowptr,
@@ -147,11 +150,14 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
                                                       const int64_t *__restrict__ part, int k,
                                                       const float *__restrict__ Ht,
                                                       const float *__restrict__ GH, float *W,
-                                                      float eps, int accumulate)
+                                                      float eps, int accumulate,
+                                                      double *__restrict__ dpart)
 {
     constexpr int LDG = 65, RPW = 64 / LPR;
     __shared__ float Gs[64 * LDG];
+    __shared__ double dsum[4];
     if (!accumulate) stage_gram(Gs, GH, k, LDG);
+    double dacc = 0.0;
     const int lane = threadIdx.x & 63;
     const int c = lane % LPR;
     const int gw = blockIdx.x * 4 + (threadIdx.x >> 6);
@@ -176,7 +182,17 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
             continue;
         }
         const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
-        if (valid && c < k) W[row * k + c] = w * acc / den;
+        if (valid && c < k) {
+            const float wn = w * acc / den;
+            W[row * k + c] = wn;
+            dacc += (double)acc * (double)wn;
+        }
+    }
+    if (dpart) {     // uniform over the grid
+        for (int off = 32; off > 0; off >>= 1) dacc += __shfl_xor(dacc, off);
+        if (lane == 0) dsum[threadIdx.x >> 6] = dacc;
+        __syncthreads();
+        if (threadIdx.x == 0) dpart[blockIdx.x] = ((dsum[0] + dsum[1]) + dsum[2]) + dsum[3];
     }
 }
 
@@ -191,13 +207,18 @@ __global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__rest
                                                            const unsigned *__restrict__ count, int k,
                                                            const float *__restrict__ Ht,
                                                            const float *__restrict__ GH, float *W,
-                                                           float eps, int accumulate)
+                                                           float eps, int accumulate,
+                                                           double *__restrict__ dpart)
 {
     constexpr int LDG = 65, NG = 256 / LPR;
     __shared__ float Gs[64 * LDG];
     __shared__ float part_acc[NG][LPR];
     const unsigned n_long = *count;
-    if (n_long == 0) return;
+    if (n_long == 0) {
+        if (dpart && threadIdx.x == 0) dpart[blockIdx.x] = 0.0;
+        return;
+    }
+    double dacc = 0.0;      // first wavefront only: it finishes the rows
     if (!accumulate) stage_gram(Gs, GH, k, LDG);
     const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     for (unsigned li = blockIdx.x; li < n_long; li += gridDim.x) {
@@ -222,10 +243,18 @@ __global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__rest
                 if (mine && c < k) W[row * k + c] = w + tot;
             } else {
                 const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
-                if (mine && c < k) W[row * k + c] = w * tot / den;
+                if (mine && c < k) {
+                    const float wn = w * tot / den;
+                    W[row * k + c] = wn;
+                    dacc += (double)tot * (double)wn;
+                }
             }
         }
         __syncthreads();
+    }
+    if (dpart && threadIdx.x < 64) {
+        for (int off = 32; off > 0; off >>= 1) dacc += __shfl_xor(dacc, off);
+        if (threadIdx.x == 0) dpart[blockIdx.x] = dacc;
     }
 }
 
@@ -369,15 +398,17 @@ hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list,
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
                           int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
-                          bool accumulate)
+                          bool accumulate, double *dpart)
 {
+    if (dpart && accumulate) return hipErrorInvalidValue;
     const int lpr = lanes_per_row(k);
     const dim3 grid(kCsrParts / 4), block(256);
     const int acc = accumulate ? 1 : 0;
+    double *dlong = dpart ? dpart + kCsrParts / 4 : nullptr;
     NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_kernel<L>), grid, block, 0, st, rowptr, colidx,
-                                             vals, part, k, Ht, GH, W, eps, acc));
-    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_long_kernel<L>), dim3(256), block, 0, st, rowptr,
-                                             colidx, vals, long_list, long_count, k, Ht, GH, W, eps, acc));
+                                             vals, part, k, Ht, GH, W, eps, acc, dpart));
+    NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_long_kernel<L>), dim3(kCsrLongBlocks), block, 0, st, rowptr,
+                                             colidx, vals, long_list, long_count, k, Ht, GH, W, eps, acc, dlong));
     return hipGetLastError();
 }
 

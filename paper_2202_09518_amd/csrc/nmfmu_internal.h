@@ -111,6 +111,8 @@ hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const fl
 constexpr int kCsrParts = 16384;      // row ranges (= wavefronts) of a sparse update launch
 constexpr int64_t kRowCost = 8;       // work of a row besides its entries, in entries
 constexpr int64_t kLongRow = 16384;   // rows with more entries go to a whole workgroup
+constexpr int kCsrLongBlocks = 256;   // workgroups of the long-row kernel
+constexpr int kCsrDparts = kCsrParts / 4 + kCsrLongBlocks;
 // part[0 .. nparts]: row ranges of equal work; part[w] = first row r with
 // rowptr[r] + kRowCost * r >= w * ceil((rowptr[m] + kRowCost * m) / nparts), part[nparts] = m.
 hipError_t launch_csr_partition(const int64_t *rowptr, int64_t m, int nparts, int64_t *part,
@@ -121,8 +123,10 @@ hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list,
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
                           int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
-                          bool accumulate = false);
+                          bool accumulate = false, double *dpart = nullptr);
 // accumulate: X[i][:] += (gathered sum) instead of the update (GH unused).
+// dpart (updating launch only; kCsrDparts doubles): per workgroup of the two kernels, the sum of
+// gathered sum x new value over its rows, i.e. <A H^T, W_new> in pieces (objective monitor).
 // X[i][:] <- X[i][:] * Num[i][:] / (X[i][:] G + eps), i < rows (X, Num rows x k).
 hipError_t launch_row_update(float *X, const float *Num, const float *G, int k, int64_t rows, float eps,
                              hipStream_t st);

@@ -72,15 +72,19 @@ def test_config3_full_size_one_iteration():
     W, H = nmf_inputs.init_factors(m, n, k, seed=2003, device="cuda")
     rp0, ci0, va0 = rowptr.clone(), colidx.clone(), vals.clone()
     W0, H0 = W.cpu().numpy(), H.cpu().numpy()
-    nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, 1, EPS)
+    obj = nmf.nmf_mu_csr_monitor(rowptr, colidx, vals, m, n, nnz, k, W, H, 1, EPS)[0]   # W, H as nmf_mu_csr gives them
     torch.cuda.synchronize()
     assert torch.equal(rowptr, rp0) and torch.equal(colidx, ci0) and torch.equal(vals, va0)
     del rp0, ci0, va0
     say(f"config 3: nnz = {nnz}; running the oracle (about a minute)")
-    Wr, Hr = orc.mu_csr(rowptr.cpu().numpy(), colidx.cpu().numpy(), vals.cpu().numpy(), m, n, W0, H0, 1, EPSD)
+    rph, cih, vah = rowptr.cpu().numpy(), colidx.cpu().numpy(), vals.cpu().numpy()
+    Wr, Hr = orc.mu_csr(rph, cih, vah, m, n, W0, H0, 1, EPSD)
     ew, eh = errs(W, H, Wr, Hr)
-    say(f"config 3 full size, 1 iteration: rel err W {ew:.2e} H {eh:.2e}")
+    want = orc.residual_csr(rph, cih, vah, m, n, Wr, Hr)
+    say(f"config 3 full size, 1 iteration: rel err W {ew:.2e} H {eh:.2e}; objective {obj:.8g} against {want:.8g}")
     assert max(ew, eh) < 1e-5
+    assert abs(obj - want) <= 1e-5 * want
+    del rph, cih, vah
     # the same matrix streamed from pinned host memory in batches of 32 Mi stored entries
     # (the launch configuration of bench.py --workload c3ooc), against the same oracle result
     rp, ci, va = rowptr.cpu().pin_memory(), colidx.cpu().pin_memory(), vals.cpu().pin_memory()

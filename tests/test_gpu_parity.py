@@ -6,6 +6,8 @@ with the fp32 result widened to double.  Bars (from the target statement):
 count.  Single products are held to 1e-5 as well (fp32 accumulation over at
 most a few thousand terms per chain, then tree sums).
 """
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -751,6 +753,67 @@ def test_csr_empty_matrix():
     assert rc == 0
     assert (host(Wd) == 0).all() and (host(Hd) == 0).all()
     del ci, va
+
+
+def csr_monitor_case(rowptr, colidx, vals, m, n, W, H, iters):
+    """Monitored sparse run against the oracle's trajectory (objective over all m n entries,
+    from the dense copy of A) and against the plain run (same bits)."""
+    import scipy.sparse as sp
+    k = W.shape[1]
+    Ad = np.asarray(sp.csr_matrix((vals, colidx, rowptr), shape=(m, n)).todense(), dtype=np.float32)
+    eps = float(np.float32(EPS))
+    want, Wr, Hr = [], W, H
+    for _ in range(iters):
+        Wr, Hr = orc.mu_csr(rowptr, colidx, vals, m, n, Wr, Hr, 1, eps)
+        want.append(orc.residual_dense(Ad, Wr, Hr))
+    want = np.array(want)
+    Wd, Hd = dev(W), dev(H)
+    got = np.array(nmf.nmf_mu_csr_monitor(dev(rowptr, torch.int64), dev(colidx, torch.int32), dev(vals), m, n,
+                                          int(vals.size), k, Wd, Hd, iters, EPS))
+    normA2 = float(np.sum(vals.astype(np.float64) ** 2))
+    bound = np.maximum(1e-5 * want, 3e-7 * normA2 / np.maximum(want, 1e-300))
+    assert (np.abs(got - want) <= bound).all(), (got, want)
+    Wg, Hg = run_csr(rowptr, colidx, vals, m, n, W, H, iters)
+    np.testing.assert_array_equal(host(Wd), Wg)
+    np.testing.assert_array_equal(host(Hd), Hg)
+
+
+@pytest.mark.parametrize("m,n,k,density,iters", [
+    (64, 48, 4, 0.3, 6), (500, 700, 32, 0.05, 4), (300, 1000, 64, 0.05, 3), (2000, 1500, 33, 0.01, 3),
+])
+def test_csr_monitor_reports_the_objective_of_every_iteration(m, n, k, density, iters):
+    rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(m, n, density, seed=190))
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=191))
+    csr_monitor_case(rowptr, colidx, vals, m, n, W, H, iters)
+
+
+def test_csr_monitor_with_long_rows_and_empty_rows():
+    """Rows above the long-row threshold are finished by another kernel, which reports its own
+    share of <A H^T, W>."""
+    r = np.random.default_rng(177)
+    m, n, k = 300, 30000, 16
+    counts = np.minimum((r.pareto(1.2, m) * 8).astype(np.int64), n)
+    counts[7] = 21000
+    counts[200] = 16500
+    counts[201] = 0
+    rows = [np.sort(r.choice(n, int(c), replace=False)).astype(np.int32) for c in counts]
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(counts)
+    colidx = np.concatenate(rows)
+    vals = (1.0 - r.random(colidx.size, dtype=np.float32)).astype(np.float32)
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=178))
+    csr_monitor_case(rowptr, colidx, vals, m, n, W, H, 3)
+
+
+def test_csr_monitor_empty_matrix():
+    m, n, k = 20, 30, 3
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=97))
+    Wd, Hd = dev(W), dev(H)
+    out = (ctypes.c_double * 2)(7.0, 7.0)
+    rc = nmf.lib().nmf_mu_csr_monitor(dev(np.zeros(m + 1, dtype=np.int64), torch.int64).data_ptr(), None, None, m, n, 0,
+                                      k, Wd.data_ptr(), Hd.data_ptr(), 2, EPS, out, None)
+    assert rc == 0 and list(out) == [0.0, 0.0]
+    assert (host(Wd) == 0).all() and (host(Hd) == 0).all()
 
 
 # ---- ensemble ----------------------------------------------------------------------

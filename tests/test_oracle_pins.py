@@ -273,6 +273,29 @@ def test_residual_is_the_frobenius_norm():
     assert abs(orc.residual_dense(A, W, H) - want) <= 1e-13 * want
 
 
+@pytest.mark.parametrize("m,n,k,density,seed", [(7, 9, 2, 0.4, 1), (40, 30, 5, 0.1, 2), (30, 50, 3, 0.0, 3)])
+def test_sparse_residual_is_the_frobenius_norm_over_all_entries(m, n, k, density, seed):
+    """The expansion the sparse objective uses against the definition on the dense copy of A
+    (zeros of A count: ||W H|| enters in full)."""
+    r = np.random.default_rng(seed)
+    Ad = (r.random((m, n)) * (r.random((m, n)) < density)).astype(np.float32)
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    cols, vals = [], []
+    for i in range(m):
+        nz = np.nonzero(Ad[i])[0]
+        cols.append(nz.astype(np.int32))
+        vals.append(Ad[i, nz])
+        rowptr[i + 1] = rowptr[i] + nz.size
+    colidx = np.concatenate(cols) if cols else np.zeros(0, np.int32)
+    v = np.concatenate(vals).astype(np.float32) if vals else np.zeros(0, np.float32)
+    W = r.random((m, k))
+    H = r.random((k, n))
+    want = np.sqrt(((Ad.astype(np.float64) - W @ H) ** 2).sum())
+    got = orc.residual_csr(rowptr, colidx, v, m, n, W, H)
+    assert abs(got - want) <= 1e-12 * want
+    assert abs(got - orc.residual_dense(Ad, W, H)) <= 1e-12 * want
+
+
 def test_half_steps_compose_to_one_iteration():
     A, W, H = small_case(9, 7, 3, 66)
     W1, H1 = orc.h_step_dense(A, W, H, EPS)
