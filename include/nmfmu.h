@@ -184,6 +184,23 @@ int nmf_mu_csr_monitor(const int64_t *rowptr, const int32_t *colidx, const float
                        double *objective_host, void *stream);
 
 /*
+ * Algorithm 1's loop on a CSR matrix, read as for nmf_mu_dense_tol: iterate until
+ * ||A - W H||_F <= tol or max_iters iterations have run; the objective is evaluated
+ * before the first iteration (one pass over the stored entries that updates
+ * nothing) and after every `check_every` iterations (the expansion of
+ * nmf_mu_csr_monitor: no extra pass over A, one stream synchronisation).  There is
+ * no cheaper exact form for a sparse A, so the stopping decision carries that
+ * expansion's error (about 2e-7 ||A||^2 / f absolute).  On return
+ * *iters_done_host iterations have been applied to W, H and *residual_host is the
+ * objective of the returned factors.  Blocking.
+ */
+int nmf_mu_csr_tol(const int64_t *rowptr, const int32_t *colidx, const float *vals,
+                   int64_t m, int64_t n, int64_t nnz, int32_t k,
+                   float *W, float *H, int32_t max_iters, float eps, double tol,
+                   int32_t check_every, int32_t *iters_done_host, double *residual_host,
+                   void *stream);
+
+/*
  * Out-of-memory dense MU: A stays in host memory and is streamed to the device
  * in batches of `batch_rows` rows (co-linear batching, Algorithm 5; W and H
  * stay resident on the device).  Each sweep uploads A once: a batch first gets

@@ -268,6 +268,22 @@ def mu_dense_tol(A, W0, H0, max_iters, eps, tol, check_every=1):
     return W, H, done, res
 
 
+def mu_csr_tol(rowptr, colidx, vals, m, n, W0, H0, max_iters, eps, tol, check_every=1):
+    """Algorithm 1's loop on a CSR matrix, as mu_dense_tol: the objective (over all
+    m n entries, residual_csr) is looked at before the first iteration and after
+    every `check_every` iterations.  Returns (W, H, iterations applied, final objective)."""
+    W = _f64(W0)
+    H = _f64(H0)
+    done = 0
+    res = residual_csr(rowptr, colidx, vals, m, n, W, H)
+    while done < max_iters and res > tol:
+        chunk = min(check_every, max_iters - done)
+        W, H = mu_csr(rowptr, colidx, vals, m, n, W, H, chunk, eps)
+        done += chunk
+        res = residual_csr(rowptr, colidx, vals, m, n, W, H)
+    return W, H, done, res
+
+
 def mu_ensemble(As, W0s, H0s, iters, eps):
     """Independent runs, one after another (NMFk-style ensemble)."""
     return [mu_dense(A, W0, H0, iters, eps) for A, W0, H0 in zip(As, W0s, H0s)]

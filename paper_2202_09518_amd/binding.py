@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_csr_monitor", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_csr_monitor", "nmf_mu_csr_tol", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_csr_partition", "nmf_split_planes", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -55,6 +55,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_mu_dense_tol.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
     L.nmf_mu_csr.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp]
     L.nmf_mu_csr_monitor.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp, vp]
+    L.nmf_mu_csr_tol.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
     L.nmf_mu_ooc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
     L.nmf_mu_dense_monitor.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_mu_csr_ooc.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
@@ -154,6 +155,18 @@ def nmf_mu_csr_monitor(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, str
                                     _dev(W, torch.float32, "W"), _dev(H, torch.float32, "H"),
                                     iters, eps, out, _stream(stream)))
     return list(out)[:iters]
+
+
+def nmf_mu_csr_tol(rowptr, colidx, vals, m, n, nnz, k, W, H, max_iters, eps, tol, check_every=1, stream=None):
+    """Algorithm 1's loop on a CSR matrix; returns (iterations applied, final objective).  Blocking."""
+    done = ctypes.c_int32(0)
+    res = ctypes.c_double(0.0)
+    _check(lib().nmf_mu_csr_tol(_dev(rowptr, torch.int64, "rowptr"), _dev(colidx, torch.int32, "colidx"),
+                                _dev(vals, torch.float32, "vals"), m, n, nnz, k,
+                                _dev(W, torch.float32, "W"), _dev(H, torch.float32, "H"),
+                                max_iters, eps, tol, check_every, ctypes.byref(done), ctypes.byref(res),
+                                _stream(stream)))
+    return done.value, res.value
 
 
 def nmf_mu_ooc(A_host, m, n, k, W, H, iters, eps, batch_rows, device_budget_bytes, stream=None) -> None:

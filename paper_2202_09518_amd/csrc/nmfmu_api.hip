@@ -925,22 +925,32 @@ size_t csr_monitor_bytes(int iters)
            align_up((size_t)iters * sizeof(double));
 }
 
-// Resident sparse run; objective_host (iters doubles) == nullptr: no monitoring.
+// Stopping rule of a sparse run (Algorithm 1): results in host memory.
+struct CsrTol {
+    double tol;
+    int check_every;
+    int32_t *iters_done;
+    double *residual;
+};
+
+// Resident sparse run; objective_host (iters doubles) == nullptr: no monitoring; with `tolp`
+// the run stops as soon as a check finds the objective at or below tolp->tol (iters = the most).
 static int csr_run(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
                    int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t iters, float eps,
-                   double *objective_host, void *stream)
+                   double *objective_host, void *stream, const CsrTol *tolp = nullptr)
 {
     if (!rowptr) return fail(NMF_EINVAL, "null pointer%s");
     if (nnz < 0) return fail(NMF_EINVAL, "nnz must be >= 0%s");
     if (nnz > 0 && (!colidx || !vals)) return fail(NMF_EINVAL, "null pointer%s");
     if (int rc = check_common(rowptr, W, H, m, n, k, iters, eps)) return rc;
-    if (iters == 0) return NMF_OK;
+    if (iters == 0 && !tolp) return NMF_OK;
     hipStream_t st = static_cast<hipStream_t>(stream);
     std::lock_guard<std::mutex> lock(g.mu);
     if (nnz >= ((int64_t)1 << 31) || m >= ((int64_t)1 << 31))
         return fail(NMF_EUNSUPPORTED, "CSR path needs nnz < 2^31 and m < 2^31%s");
     void *ws = nullptr;
-    if (int rc = ensure_workspace(csr_bytes(n, nnz, k) + (objective_host ? csr_monitor_bytes(iters) : 0), &ws))
+    const bool watch = objective_host || tolp;
+    if (int rc = ensure_workspace(csr_bytes(n, nnz, k) + (watch ? csr_monitor_bytes(tolp ? 1 : iters) : 0), &ws))
         return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
@@ -954,10 +964,10 @@ static int csr_run(const int64_t *rowptr, const int32_t *colidx, const float *va
     int32_t *long_c = cv.take<int32_t>((size_t)(nnz / kLongRow + 2));
     unsigned *long_n = cv.take<unsigned>(64);      // [0] rows of A, [1] columns of A
     double *dpart = nullptr, *normA2 = nullptr, *obj = nullptr;
-    if (objective_host) {
+    if (watch) {
         dpart = cv.take<double>(kCsrDparts);
         normA2 = cv.take<double>(4097);
-        obj = cv.take<double>((size_t)iters);
+        obj = cv.take<double>(tolp ? 1 : (size_t)iters);
         if (nnz > 0) NMF_HIP(launch_sumsq(vals, nnz, normA2 + 1, normA2, st));
         else NMF_HIP(hipMemsetAsync(normA2, 0, sizeof(double), st));
     }
@@ -971,21 +981,49 @@ static int csr_run(const int64_t *rowptr, const int32_t *colidx, const float *va
     NMF_HIP(launch_csr_long_rows(colptr, n, long_c, long_n + 1, st));
 
     NMF_HIP(launch_transpose(H, k, n, Ht, st));
-    for (int it = 0; it < iters; ++it) {
+    // One iteration; with `out`, ||A - W H||_F of its result goes there, from what the W update
+    // leaves behind: <A H^T, W>, H H^T, and W^T W of the new W (computed here; the next iteration
+    // computes the same matrix again for its H update).
+    auto iteration = [&](double *out) -> int {
         NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
         NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, W, c.gw, Ht, eps, st));   // H update on H^T
         NMF_HIP(launch_gram_w_wide(Ht, n, k, c.gh, c.ghp, st));
         NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st, false,
-                               dpart));                                                                       // W update
-        if (dpart) {
-            // ||A - W H||_F from what the W update leaves behind: <A H^T, W>, H H^T, and W^T W of the
-            // new W (computed here; the next iteration computes the same matrix again for its H update)
+                               out ? dpart : nullptr));                                                       // W update
+        if (out) {
             NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
-            NMF_HIP(launch_objective(dpart, kCsrDparts, c.gw, c.gh, k, normA2, obj + it, st));
+            NMF_HIP(launch_objective(dpart, kCsrDparts, c.gw, c.gh, k, normA2, out, st));
         }
+        return NMF_OK;
+    };
+    if (tolp) {
+        // objective of the factors as given: the W pass without its update
+        double res = 0.0;
+        NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
+        NMF_HIP(launch_gram_w_wide(Ht, n, k, c.gh, c.ghp, st));
+        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st, false, dpart, true));
+        NMF_HIP(launch_objective(dpart, kCsrDparts, c.gw, c.gh, k, normA2, obj, st));
+        NMF_HIP(hipMemcpyAsync(&res, obj, sizeof(double), hipMemcpyDeviceToHost, st));
+        NMF_HIP(hipStreamSynchronize(st));
+        int done = 0;
+        while (done < iters && res > tolp->tol) {
+            const int chunk = (iters - done < tolp->check_every) ? iters - done : tolp->check_every;
+            for (int it = 0; it < chunk; ++it)
+                if (int rc = iteration(it == chunk - 1 ? obj : nullptr)) return rc;
+            NMF_HIP(hipMemcpyAsync(&res, obj, sizeof(double), hipMemcpyDeviceToHost, st));
+            NMF_HIP(hipStreamSynchronize(st));
+            done += chunk;
+        }
+        NMF_HIP(launch_transpose(Ht, n, k, H, st));
+        NMF_HIP(hipStreamSynchronize(st));
+        *tolp->iters_done = done;
+        *tolp->residual = res;
+        return NMF_OK;
     }
+    for (int it = 0; it < iters; ++it)
+        if (int rc = iteration(objective_host ? obj + it : nullptr)) return rc;
     NMF_HIP(launch_transpose(Ht, n, k, H, st));
-    if (dpart) {
+    if (objective_host) {
         NMF_HIP(hipMemcpyAsync(objective_host, obj, (size_t)iters * sizeof(double), hipMemcpyDeviceToHost, st));
         NMF_HIP(hipStreamSynchronize(st));
     }
@@ -1006,6 +1044,19 @@ int nmf_mu_csr_monitor(const int64_t *rowptr, const int32_t *colidx, const float
     if (!objective_host) return fail(NMF_EINVAL, "null pointer%s");
     if (iters > (1 << 20)) return fail(NMF_EINVAL, "monitored run: iters <= 2^20%s");
     return csr_run(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, objective_host, stream);
+}
+
+int nmf_mu_csr_tol(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
+                   int64_t n, int64_t nnz, int32_t k, float *W, float *H, int32_t max_iters, float eps,
+                   double tol, int32_t check_every, int32_t *iters_done_host, double *residual_host,
+                   void *stream)
+{
+    if (!iters_done_host || !residual_host) return fail(NMF_EINVAL, "null pointer%s");
+    if (check_every < 1) return fail(NMF_EINVAL, "check_every must be >= 1%s");
+    if (!(tol >= 0.0)) return fail(NMF_EINVAL, "tol must be >= 0%s");
+    const CsrTol t = {tol, check_every, iters_done_host, residual_host};
+    *iters_done_host = 0;
+    return csr_run(rowptr, colidx, vals, m, n, nnz, k, W, H, max_iters, eps, nullptr, stream, &t);
 }
 
 // Out-of-memory CSR: row batches of about batch_nnz stored entries each, streamed from host

@@ -139,9 +139,11 @@ __device__ __forceinline__ float gather_chunk(const int32_t *__restrict__ colidx
 // Wavefront gw works on rows [part[gw], part[gw + 1]), 64 / LPR rows at a time.
 // accumulate != 0: no update; the gathered sums are added to W instead (the
 // numerator of an update collected over several row batches of the matrix; GH unused).
-// dpart (updating launch only): dpart[blockIdx.x] = sum over this block's rows of gathered
-// sum x new value in double, i.e. its share of <A H^T, W_new> for the objective
-// ||A||^2 - 2 <A H^T, W> + <H H^T, W^T W>; lanes by butterfly, then the 4 waves in order.
+// accumulate == 2: nothing is written to W (needs dpart; GH unused).
+// dpart: dpart[blockIdx.x] = sum over this block's rows of gathered sum x value of W in double
+// (the new value in an updating launch, the unchanged one with accumulate == 2), i.e. its
+// share of <A H^T, W> for the objective ||A||^2 - 2 <A H^T, W> + <H H^T, W^T W>; lanes by
+// butterfly, then the 4 waves in order.
 // ---------------------------------------------------------------------------
 template <int LPR>
 __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict__ rowptr,
@@ -177,6 +179,10 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
             e += LPR;
         }
         const float w = (valid && c < k) ? W[row * k + c] : 0.f;
+        if (accumulate == 2) {
+            if (valid && c < k) dacc += (double)acc * (double)w;
+            continue;
+        }
         if (accumulate) {
             if (valid && c < k) W[row * k + c] = w + acc;
             continue;
@@ -239,7 +245,9 @@ __global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__rest
             const float tot = part_acc[0][c];
             const bool mine = threadIdx.x < LPR;
             const float w = (mine && c < k) ? W[row * k + c] : 0.f;
-            if (accumulate) {
+            if (accumulate == 2) {
+                if (mine && c < k) dacc += (double)tot * (double)w;
+            } else if (accumulate) {
                 if (mine && c < k) W[row * k + c] = w + tot;
             } else {
                 const float den = row_times_gram<LPR>(w, Gs, LDG, k, c) + eps;
@@ -398,12 +406,12 @@ hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list,
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
                           int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
-                          bool accumulate, double *dpart)
+                          bool accumulate, double *dpart, bool dry)
 {
-    if (dpart && accumulate) return hipErrorInvalidValue;
+    if ((dpart && accumulate) || (dry && (!dpart || accumulate))) return hipErrorInvalidValue;
     const int lpr = lanes_per_row(k);
     const dim3 grid(kCsrParts / 4), block(256);
-    const int acc = accumulate ? 1 : 0;
+    const int acc = dry ? 2 : (accumulate ? 1 : 0);
     double *dlong = dpart ? dpart + kCsrParts / 4 : nullptr;
     NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_kernel<L>), grid, block, 0, st, rowptr, colidx,
                                              vals, part, k, Ht, GH, W, eps, acc, dpart));

@@ -123,10 +123,11 @@ hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list,
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
                           int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
-                          bool accumulate = false, double *dpart = nullptr);
+                          bool accumulate = false, double *dpart = nullptr, bool dry = false);
 // accumulate: X[i][:] += (gathered sum) instead of the update (GH unused).
 // dpart (updating launch only; kCsrDparts doubles): per workgroup of the two kernels, the sum of
 // gathered sum x new value over its rows, i.e. <A H^T, W_new> in pieces (objective monitor).
+// dry (needs dpart): W is left alone and dpart gets <A H^T, W> of the factors as they are.
 // X[i][:] <- X[i][:] * Num[i][:] / (X[i][:] G + eps), i < rows (X, Num rows x k).
 hipError_t launch_row_update(float *X, const float *Num, const float *G, int k, int64_t rows, float eps,
                              hipStream_t st);

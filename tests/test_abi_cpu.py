@@ -103,6 +103,10 @@ def test_argument_errors_need_no_device():
     assert L.nmf_mu_csr_monitor(one, one, one, 4, 4, 3, 2, one, one, 1, 1e-16, null, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_csr_monitor(null, one, one, 4, 4, 3, 2, one, one, 1, 1e-16, one, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_csr_monitor(one, one, one, 4, 4, 3, 2, one, one, (1 << 20) + 1, 1e-16, one, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_csr_tol(one, one, one, 4, 4, 3, 2, one, one, 5, 1e-16, 0.1, 1, null, one, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_csr_tol(one, one, one, 4, 4, 3, 2, one, one, 5, 1e-16, 0.1, 0, one, one, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_csr_tol(one, one, one, 4, 4, 3, 2, one, one, 5, 1e-16, -1.0, 1, one, one, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_csr_tol(one, one, one, 4, 4, 3, 2, one, one, 5, 1e-16, float("nan"), 1, one, one, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_dense_batched(-1, one, 4, 4, one, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_set_workspace(ctypes.c_void_p(8), 4096) == nmf.NMF_EINVAL   # misaligned
 

@@ -805,6 +805,48 @@ def test_csr_monitor_with_long_rows_and_empty_rows():
     csr_monitor_case(rowptr, colidx, vals, m, n, W, H, 3)
 
 
+@pytest.mark.parametrize("m,n,k,density,every", [(500, 700, 32, 0.05, 2), (300, 30000, 16, 0.002, 1)])
+def test_csr_tol_matches_algorithm_1_loop(m, n, k, density, every):
+    rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(m, n, density, seed=290))
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=291))
+    eps = float(np.float32(EPS))
+    nnz = int(vals.size)
+    traj = [orc.residual_csr(rowptr, colidx, vals, m, n, W, H)]
+    Wt, Ht = W, H
+    for _ in range(6):
+        Wt, Ht = orc.mu_csr(rowptr, colidx, vals, m, n, Wt, Ht, every, eps)
+        traj.append(orc.residual_csr(rowptr, colidx, vals, m, n, Wt, Ht))
+    gap = traj[3] - traj[4]
+    normA2 = float(np.sum(vals.astype(np.float64) ** 2))
+    assert gap > 50 * 3e-7 * normA2 / traj[4]      # the two checks around the tolerance are far apart for the expansion
+    tol = 0.5 * (traj[3] + traj[4])                # first met at the 4th check after the start
+    Wr, Hr, done_r, res_r = orc.mu_csr_tol(rowptr, colidx, vals, m, n, W, H, 1000, eps, tol, check_every=every)
+    rp, ci, va = dev(rowptr, torch.int64), dev(colidx, torch.int32), dev(vals)
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_csr_tol(rp, ci, va, m, n, nnz, k, Wd, Hd, 1000, EPS, tol, every)
+    assert done == done_r == 4 * every
+    assert abs(res - res_r) <= 1e-5 * res_r + 3e-7 * normA2 / res_r and res <= tol
+    check(host(Wd), host(Hd), Wr, Hr, TOL1 * done)
+    # the stopped run is the plain run of that many iterations, bit for bit
+    Wg, Hg = run_csr(rowptr, colidx, vals, m, n, W, H, done)
+    np.testing.assert_array_equal(host(Wd), Wg)
+    np.testing.assert_array_equal(host(Hd), Hg)
+    # cap reached / tolerance already met / no iterations allowed
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_csr_tol(rp, ci, va, m, n, nnz, k, Wd, Hd, 3, EPS, 0.0, 2)
+    assert done == 3
+    Wg, Hg = run_csr(rowptr, colidx, vals, m, n, W, H, 3)
+    np.testing.assert_array_equal(host(Wd), Wg)
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_csr_tol(rp, ci, va, m, n, nnz, k, Wd, Hd, 7, EPS, 1e9, 2)
+    assert done == 0 and abs(res - traj[0]) <= 1e-5 * traj[0]
+    np.testing.assert_array_equal(host(Wd), W.astype(np.float64))
+    np.testing.assert_array_equal(host(Hd), H.astype(np.float64))
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_csr_tol(rp, ci, va, m, n, nnz, k, Wd, Hd, 0, EPS, 0.0, 1)
+    assert done == 0 and abs(res - traj[0]) <= 1e-5 * traj[0]
+
+
 def test_csr_monitor_empty_matrix():
     m, n, k = 20, 30, 3
     W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=97))

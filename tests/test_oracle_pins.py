@@ -513,3 +513,32 @@ def test_tolerance_loop_stops_where_the_objective_says():
     Wn, Hn, done, res = orc.mu_dense_tol(A, W, H, 7, EPS, 1e9, check_every=5)
     assert done == 0 and res == traj[0]
     np.testing.assert_array_equal(Wn, W)
+
+
+def test_sparse_tolerance_loop_stops_where_the_objective_says():
+    """mu_csr_tol against a hand-rolled loop over mu_csr and the objective of the dense copy."""
+    import scipy.sparse as sp
+    m, n, k = 40, 30, 3
+    r = np.random.default_rng(12)
+    Ad = (r.random((m, n)) * (r.random((m, n)) < 0.3)).astype(np.float32)
+    S = sp.csr_matrix(Ad)
+    S.sort_indices()
+    rowptr, colidx, vals = S.indptr.astype(np.int64), S.indices.astype(np.int32), S.data.astype(np.float32)
+    W, H = r.random((m, k)), r.random((k, n))
+    traj = [orc.residual_dense(Ad, W, H)]
+    Wt, Ht = W, H
+    for _ in range(10):
+        Wt, Ht = orc.mu_csr(rowptr, colidx, vals, m, n, Wt, Ht, 2, EPS)
+        traj.append(orc.residual_dense(Ad, Wt, Ht))
+    assert traj[5] < traj[4]
+    tol = 0.5 * (traj[4] + traj[5])                   # first met after 5 checks = 10 iterations
+    Wo, Ho, done, res = orc.mu_csr_tol(rowptr, colidx, vals, m, n, W, H, 1000, EPS, tol, check_every=2)
+    assert done == 10 and abs(res - traj[5]) <= 1e-12 * traj[5] and res <= tol < traj[4]
+    W10, H10 = orc.mu_csr(rowptr, colidx, vals, m, n, W, H, 10, EPS)
+    np.testing.assert_array_equal(Wo, W10)
+    np.testing.assert_array_equal(Ho, H10)
+    _, _, done, _ = orc.mu_csr_tol(rowptr, colidx, vals, m, n, W, H, 7, EPS, 0.0, check_every=2)
+    assert done == 7
+    Wn, Hn, done, res = orc.mu_csr_tol(rowptr, colidx, vals, m, n, W, H, 7, EPS, 1e9, check_every=2)
+    assert done == 0 and abs(res - traj[0]) <= 1e-12 * traj[0]
+    np.testing.assert_array_equal(Wn, W)
