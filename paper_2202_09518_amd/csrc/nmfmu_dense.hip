@@ -822,9 +822,12 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
 {
     constexpr int NW = 8, KT = KP / 32 > 0 ? KP / 32 : 1, NC = (KP + 7) / 8, LD = KP + 1;
     constexpr int LDT = 32 * KT + 1;   // the Gram tiles read 32 factor indices per tile
-    __shared__ float Gs[KP * LD];
-    __shared__ float Ts[64 * LDT];
-    __shared__ float red[1024];
+    // one LDS array: G and the chunk's new values during the updates, then (after a barrier)
+    // the eight waves' copies of a Gram tile for the sum over waves
+    constexpr int GS = KP * LD, TS = 64 * LDT;
+    constexpr int SM = (GS + TS > NW * 1024) ? GS + TS : NW * 1024;
+    __shared__ float Sm[SM];
+    float *Gs = Sm, *Ts = Sm + GS;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int kt = (k + 31) >> 5;
 
@@ -995,23 +998,23 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
         }
     }
     if (!gout) return;
+    __syncthreads();   // the last chunk's readers of Ts are done: Sm changes hands
     // Rows and columns of a tile at factor indices >= k hold whatever LDS held;
     // consumers never read them.
     for (int a = 0; a < KT; ++a)
         for (int b = 0; b < KT; ++b) {
             if (a >= kt || b >= kt) continue;
-            for (int ww = 0; ww < NW; ++ww) {
-                if (w == ww) {
+            // every wave parks its tile, then all threads add the eight copies in wave order
 #pragma unroll
-                    for (int v = 0; v < 16; ++v) {
-                        if (ww == 0) red[v * 64 + lane] = acc[a][b][v];
-                        else red[v * 64 + lane] += acc[a][b][v];
-                    }
-                }
-                __syncthreads();
-            }
+            for (int v = 0; v < 16; ++v) Sm[w * 1024 + v * 64 + lane] = acc[a][b][v];
+            __syncthreads();
             float *dst = gout + ((int64_t)blockIdx.x * kt * kt + a * kt + b) * 1024;
-            for (int e = tid; e < 1024; e += 64 * NW) dst[e] = red[e];
+            for (int e = tid; e < 1024; e += 64 * NW) {
+                float t = Sm[e];
+#pragma unroll
+                for (int ww = 1; ww < NW; ++ww) t += Sm[ww * 1024 + e];
+                dst[e] = t;
+            }
             __syncthreads();
         }
 }
