@@ -222,6 +222,22 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k,
                int64_t batch_rows, int64_t device_budget_bytes, void *stream);
 
 /*
+ * nmf_mu_ooc with the objective ||A - W H||_F reported after every iteration
+ * (Algorithm 1 evaluates it every iteration), without another pass over A: the
+ * expansion ||A||^2 - 2 <A H^T, W> + <H H^T, W^T W> of nmf_mu_dense_monitor, with
+ * <A H^T, W> collected in double by the W updates of a sweep's batches, W^T W of
+ * the W they leave (one more Gram after the last sweep), H H^T of the H they
+ * used, and ||A||^2 summed batch by batch during the first sweep (one more read
+ * of each staged batch, on the device).  Absolute error about 2e-7 ||A||^2 / f.
+ * k <= NMF_MU_MAX_K.  objective_host: HOST memory, iters doubles.  Blocking.
+ * W, H as nmf_mu_ooc (bit-identical result).
+ */
+int nmf_mu_ooc_monitor(const float *A_host, int64_t m, int64_t n, int32_t k,
+                       float *W, float *H, int32_t iters, float eps,
+                       int64_t batch_rows, int64_t device_budget_bytes,
+                       double *objective_host, void *stream);
+
+/*
  * Out-of-memory dense MU with W in host memory as well (Algorithm 5 as printed:
  * per batch, W_b and A_b go to the device, W_b is updated and copied back, and
  * W_b^T A_b, W_b^T W_b are accumulated for the H update; section 4.4 is the

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_csr_monitor", "nmf_mu_csr_tol", "nmf_mu_ooc", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_csr_monitor", "nmf_mu_csr_tol", "nmf_mu_ooc", "nmf_mu_ooc_monitor", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_csr_partition", "nmf_split_planes", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -57,6 +57,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_mu_csr_monitor.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_mu_csr_tol.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
     L.nmf_mu_ooc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
+    L.nmf_mu_ooc_monitor.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp, vp]
     L.nmf_mu_dense_monitor.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_mu_csr_ooc.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, vp, i32, f32, i64, i64, vp]
     L.nmf_mu_ooc_hostw.argtypes = [vp, vp, i64, i64, i32, vp, i32, f32, i64, i32, vp, vp]
@@ -145,6 +146,17 @@ def nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, stream=None
                             _dev(vals, torch.float32, "vals"), m, n, nnz, k,
                             _dev(W, torch.float32, "W"), _dev(H, torch.float32, "H"),
                             iters, eps, _stream(stream)))
+
+
+def nmf_mu_ooc_monitor(A_host, m, n, k, W, H, iters, eps, batch_rows, device_budget_bytes, stream=None):
+    """nmf_mu_ooc that also returns the objective after each iteration (list of floats, blocking)."""
+    if A_host.is_cuda or A_host.dtype != torch.float32 or not A_host.is_contiguous():
+        raise ValueError("A_host: need a contiguous float32 host tensor (pinned for overlap)")
+    out = (ctypes.c_double * max(iters, 1))()
+    _check(lib().nmf_mu_ooc_monitor(A_host.data_ptr(), m, n, k, _dev(W, torch.float32, "W"),
+                                    _dev(H, torch.float32, "H"), iters, eps, batch_rows,
+                                    device_budget_bytes, out, _stream(stream)))
+    return list(out)[:iters]
 
 
 def nmf_mu_csr_monitor(rowptr, colidx, vals, m, n, nnz, k, W, H, iters, eps, stream=None):

@@ -822,11 +822,15 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
     return NMF_OK;
 }
 
-int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, float *H,
-               int32_t iters, float eps, int64_t batch_rows, int64_t device_budget_bytes,
-               void *stream)
+// Streamed dense run; objective_host (iters doubles) != nullptr: the objective of every
+// iteration as well (ranks up to NMF_MU_MAX_K only).
+static int ooc_run(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                   int32_t iters, float eps, int64_t batch_rows, int64_t device_budget_bytes,
+                   double *objective_host, void *stream)
 {
     if (int rc = check_common(A_host, W, H, m, n, k, iters, eps, NMF_MU_MAX_K_SLICED)) return rc;
+    if (objective_host && k > NMF_MU_MAX_K)
+        return fail(NMF_EUNSUPPORTED, "monitored out-of-memory run: k <= 64%s");
     if (batch_rows < 1) return fail(NMF_EINVAL, "batch_rows must be >= 1%s");
     if (device_budget_bytes < 1) return fail(NMF_EINVAL, "device_budget_bytes must be >= 1%s");
     if (iters == 0) return NMF_OK;
@@ -843,14 +847,29 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
         if (slots > nbat) slots = (int)nbat;
         return sliced_ooc_run(A_host, nullptr, W, m, n, k, H, iters, eps, batch_rows, slots, st, nullptr);
     }
+    const int64_t nb = (m + batch_rows - 1) / batch_rows;
+    // monitored run: the W updates' shares of <A H^T, W> (one per workgroup and batch), ||A_b||^2 per
+    // batch and its scratch, ||A||^2, one objective value per iteration
+    const int64_t bpb = aht_pass_blocks(batch_rows);
+    const size_t mon_bytes = objective_host
+        ? align_up((size_t)(nb * bpb) * sizeof(double)) + align_up((size_t)nb * sizeof(double)) +
+          align_up(4097 * sizeof(double)) + align_up((size_t)iters * sizeof(double))
+        : 0;
     void *ws = nullptr;
-    if (int rc = ensure_workspace(dense_bytes(batch_rows, n, k, false), &ws)) return rc;
+    if (int rc = ensure_workspace(dense_bytes(batch_rows, n, k, false) + mon_bytes, &ws)) return rc;
     Carve cv(ws);
     const Common c = carve_common(cv, k);
     const int splits = wta_splits(batch_rows, n, k);
     const int64_t rps = wta_rows_per_split(batch_rows, splits);
     float *ppart = cv.take<float>((size_t)splits * k * n);
     void *planes = cv.take<char>(planes_bytes(batch_rows));
+    double *dpart = nullptr, *normb = nullptr, *normA2 = nullptr, *obj = nullptr;
+    if (objective_host) {
+        dpart = cv.take<double>((size_t)(nb * bpb));
+        normb = cv.take<double>((size_t)nb);
+        normA2 = cv.take<double>(4097);
+        obj = cv.take<double>((size_t)iters);
+    }
 
     if (g.stage_bytes < slots * slot_bytes) {
         if (g.stage) {
@@ -873,7 +892,6 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
     NMF_HIP(hipEventRecord(g.ev_entry, st));
     NMF_HIP(hipStreamWaitEvent(g.copy_stream, g.ev_entry, 0));
 
-    const int64_t nb = (m + batch_rows - 1) / batch_rows;
     int64_t issued = 0;   // batches handed to the copy stream so far, over all sweeps
     for (int s = 0; s <= iters; ++s) {
         for (int64_t b = 0; b < nb; ++b, ++issued) {
@@ -886,18 +904,53 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, f
                                    hipMemcpyHostToDevice, g.copy_stream));
             NMF_HIP(hipEventRecord(g.ev_copied[slot], g.copy_stream));
             NMF_HIP(hipStreamWaitEvent(st, g.ev_copied[slot], 0));
-            if (s > 0) NMF_HIP(launch_aht_pass(Ab, rb, n, k, H, c.gh, W + i0 * k, eps, st));
+            if (dpart && s == 0) NMF_HIP(launch_sumsq(Ab, rb * n, normA2 + 1, normb + b, st));
+            if (s > 0)
+                NMF_HIP(launch_aht_pass(Ab, rb, n, k, H, c.gh, W + i0 * k, eps, st, dpart ? dpart + b * bpb : nullptr));
             if (s < iters)
                 NMF_HIP(launch_wta_pass(Ab, rb, n, k, W + i0 * k, planes, false, ppart, splits, rps, b > 0, st));
             NMF_HIP(hipEventRecord(g.ev_freed[slot], st));
         }
+        if (dpart && s == 0) NMF_HIP(launch_sum_f64(normb, nb, normA2, st));
+        if (s < iters || dpart) NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
+        if (dpart && s > 0) {
+            // iteration s is complete: <A H^T, W> from this sweep's W updates (a short last batch
+            // leaves the tail of its segment untouched, so its workgroups are counted, not bpb),
+            // H H^T of the H they used, W^T W of the W they left
+            const int64_t last_rows = m - (nb - 1) * batch_rows;
+            if (aht_pass_blocks(last_rows) != bpb) {
+                // close the gap so that the shares are one contiguous run
+                NMF_HIP(hipMemsetAsync(dpart + (nb - 1) * bpb + aht_pass_blocks(last_rows), 0,
+                                       (size_t)(bpb - aht_pass_blocks(last_rows)) * sizeof(double), st));
+            }
+            NMF_HIP(launch_objective(dpart, (int)(nb * bpb), c.gw, c.gh, k, normA2, obj + (s - 1), st));
+        }
         if (s < iters) {
-            NMF_HIP(launch_gram_w(W, m, k, c.gw, c.gpart, c.counters, st));
             NMF_HIP(launch_factor_update(H, nullptr, ppart, splits, c.gw, nullptr, 0, nullptr, k, n, eps, st));
             NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
         }
     }
+    if (dpart) {
+        NMF_HIP(hipMemcpyAsync(objective_host, obj, (size_t)iters * sizeof(double), hipMemcpyDeviceToHost, st));
+        NMF_HIP(hipStreamSynchronize(st));
+    }
     return NMF_OK;
+}
+
+int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, float *H,
+               int32_t iters, float eps, int64_t batch_rows, int64_t device_budget_bytes,
+               void *stream)
+{
+    return ooc_run(A_host, m, n, k, W, H, iters, eps, batch_rows, device_budget_bytes, nullptr, stream);
+}
+
+int nmf_mu_ooc_monitor(const float *A_host, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                       int32_t iters, float eps, int64_t batch_rows, int64_t device_budget_bytes,
+                       double *objective_host, void *stream)
+{
+    if (!objective_host) return fail(NMF_EINVAL, "null pointer%s");
+    if (iters > (1 << 20)) return fail(NMF_EINVAL, "monitored run: iters <= 2^20%s");
+    return ooc_run(A_host, m, n, k, W, H, iters, eps, batch_rows, device_budget_bytes, objective_host, stream);
 }
 
 int nmf_mu_ooc_hostw(const float *A_host, float *W_host, int64_t m, int64_t n, int32_t k, float *H,

@@ -1028,12 +1028,15 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
 // pattern: lane l, load u -> row l % 32, columns jb + 8u + 4 (l / 32) .. +3.
 // Epilogue: waves summed through LDS in wave order, then
 //   W[i][c] <- W[i][c] * Q[i][c] / (sum_d W[i][d] GH[d][c] + eps).
+// dpart != nullptr: dpart[blockIdx.x] = sum over the block's entries of Q x new W in double
+// (its share of <A H^T, W_new> for the objective), lanes by butterfly, then the waves in order.
 // ---------------------------------------------------------------------------
 template <int KT, int RT, bool VEC>
 __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__ A,
                                                        const float *__restrict__ H,
                                                        const float *__restrict__ GH, float *W,
-                                                       int64_t rows, int64_t n, int k, float eps)
+                                                       int64_t rows, int64_t n, int k, float eps,
+                                                       double *__restrict__ dpart)
 {
     constexpr int NW = kAhtWaves;
     constexpr int RB = 32 * RT;
@@ -1117,6 +1120,7 @@ __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__
         __syncthreads();
     }
 
+    double dacc = 0.0;
     for (int e = tid; e < RB * k; e += 512) {
         const int i = e / k, c = e % k;
         if (i0 + i < rows) {
@@ -1127,7 +1131,20 @@ __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__
             }
             if (k & 1) d0 += Ws[i * LDQ + k - 1] * Gs[(k - 1) * LDQ + c];
             const float den = (d0 + d1) + eps;
-            W[(i0 + i) * k + c] = Ws[i * LDQ + c] * Qs[i * LDQ + c] / den;
+            const float wn = Ws[i * LDQ + c] * Qs[i * LDQ + c] / den;
+            W[(i0 + i) * k + c] = wn;
+            dacc += (double)Qs[i * LDQ + c] * (double)wn;
+        }
+    }
+    if (dpart) {     // uniform over the grid
+        __shared__ double dsum[NW];
+        for (int off = 32; off > 0; off >>= 1) dacc += __shfl_xor(dacc, off);
+        if (lane == 0) dsum[w] = dacc;
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0.0;
+            for (int ww = 0; ww < NW; ++ww) t += dsum[ww];
+            dpart[blockIdx.x] = t;
         }
     }
 }
@@ -1747,26 +1764,33 @@ hipError_t launch_residual(const float *A, int64_t m, int64_t n, int k, const fl
 
 template <int KT>
 static void aht_dispatch(bool vec, dim3 grid, hipStream_t st, const float *A, const float *H,
-                         const float *GH, float *W, int64_t rows, int64_t n, int k, float eps)
+                         const float *GH, float *W, int64_t rows, int64_t n, int k, float eps, double *dpart)
 {
     constexpr int RT = kAhtRowTiles;
     if (vec)
-        hipLaunchKernelGGL((aht_pass_kernel<KT, RT, true>), grid, dim3(512), 0, st, A, H, GH, W, rows, n, k, eps);
+        hipLaunchKernelGGL((aht_pass_kernel<KT, RT, true>), grid, dim3(512), 0, st, A, H, GH, W, rows, n, k, eps, dpart);
     else
-        hipLaunchKernelGGL((aht_pass_kernel<KT, RT, false>), grid, dim3(512), 0, st, A, H, GH, W, rows, n, k, eps);
+        hipLaunchKernelGGL((aht_pass_kernel<KT, RT, false>), grid, dim3(512), 0, st, A, H, GH, W, rows, n, k, eps, dpart);
 }
 
+int64_t aht_pass_blocks(int64_t rows) { return (rows + 32 * kAhtRowTiles - 1) / (32 * kAhtRowTiles); }
+
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
-                           const float *GH, float *W, float eps, hipStream_t st)
+                           const float *GH, float *W, float eps, hipStream_t st, double *dpart)
 {
-    const int rb = 32 * kAhtRowTiles;
-    dim3 grid((unsigned)((rows + rb - 1) / rb));
+    dim3 grid((unsigned)aht_pass_blocks(rows));
     const bool vec = vec_ok(A, n) && vec_ok(H, n);
     switch (k_tiles(k)) {
-    case 1: aht_dispatch<1>(vec, grid, st, A, H, GH, W, rows, n, k, eps); break;
-    case 2: aht_dispatch<2>(vec, grid, st, A, H, GH, W, rows, n, k, eps); break;
+    case 1: aht_dispatch<1>(vec, grid, st, A, H, GH, W, rows, n, k, eps, dpart); break;
+    case 2: aht_dispatch<2>(vec, grid, st, A, H, GH, W, rows, n, k, eps, dpart); break;
     default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_sum_f64(const double *in, int64_t count, double *out, hipStream_t st)
+{
+    hipLaunchKernelGGL(sum_f64_kernel, dim3(1), dim3(64), 0, st, in, count, out);
     return hipGetLastError();
 }
 

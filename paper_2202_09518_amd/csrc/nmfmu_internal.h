@@ -96,8 +96,12 @@ hipError_t launch_gram_sum(const float *gpart, int nb, int k, float *G, hipStrea
 // writes the partial tiles to gpart.
 int gram_w_blocks(int64_t rows);
 // W <- W * (A H^T) / (W GH + eps), in place, for `rows` rows of A and W.
+// dpart (aht_pass_blocks(rows) doubles): per workgroup, the sum of (A H^T) x new W over its rows.
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
-                           const float *GH, float *W, float eps, hipStream_t st);
+                           const float *GH, float *W, float eps, hipStream_t st, double *dpart = nullptr);
+int64_t aht_pass_blocks(int64_t rows);
+// out[0] = in[0] + ... + in[count - 1], added in index order.
+hipError_t launch_sum_f64(const double *in, int64_t count, double *out, hipStream_t st);
 
 // out[0] = ||A - W H||_F; partial: residual_partials(m, n) doubles of scratch.
 int64_t residual_partials(int64_t m, int64_t n);

@@ -97,6 +97,9 @@ def test_argument_errors_need_no_device():
     assert L.nmf_mu_ooc(one, 4, 4, 2, one, one, 1, 1e-16, 0, 1 << 20, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_ooc(one, 4, 4, 2, one, one, 1, 1e-16, 2, 0, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_ooc(one, 4, 4, 2, one, one, 1, 1e-16, 2, 8, null) == nmf.NMF_ENOMEM
+    assert L.nmf_mu_ooc_monitor(one, 4, 4, 2, one, one, 1, 1e-16, 2, 1 << 20, null, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_ooc_monitor(one, 4, 4, 2, one, one, 1, 1e-16, 0, 1 << 20, one, null) == nmf.NMF_EINVAL
+    assert L.nmf_mu_ooc_monitor(one, 4, 4, 70, one, one, 1, 1e-16, 2, 1 << 20, one, null) == nmf.NMF_EUNSUPPORTED
     assert L.nmf_mu_csr(null, one, one, 4, 4, 3, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_csr(one, null, one, 4, 4, 3, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL
     assert L.nmf_mu_csr(one, one, one, 4, 4, -1, 2, one, one, 1, 1e-16, null) == nmf.NMF_EINVAL

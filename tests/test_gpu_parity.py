@@ -365,6 +365,41 @@ def test_ooc_matches_oracle(m, n, k, batch, slots, iters):
     check(host(Wd), host(Hd), Wr, Hr, TOL1 * iters)
 
 
+@pytest.mark.parametrize("m,n,k,batch,slots,iters", [
+    (1000, 520, 32, 256, 3, 5),     # ragged last batch: its workgroups leave a gap in the list of shares
+    (777, 260, 64, 100, 2, 3),
+    (256, 192, 4, 48, 3, 30),
+    (640, 512, 17, 640, 1, 3),      # one batch
+    (130, 70, 5, 1, 2, 2),          # one row per batch
+])
+def test_ooc_monitor_reports_the_objective_of_every_iteration(m, n, k, batch, slots, iters):
+    if (m, n, k) == (256, 192, 4):
+        A, W, H = config1()
+    else:
+        A, W, H = case(m, n, k, 71)
+    want, Wr, Hr = oracle_trajectory(A, W, H, iters)
+    Ah = torch.from_numpy(A).pin_memory()
+    budget = slots * (((min(batch, m) * n * 4) + 255) // 256 * 256)
+    Wd, Hd = dev(W), dev(H)
+    got = np.array(nmf.nmf_mu_ooc_monitor(Ah, m, n, k, Wd, Hd, iters, EPS, batch, budget))
+    normA2 = float(np.sum(A.astype(np.float64) ** 2))
+    bound = np.maximum(1e-5 * want, 3e-7 * normA2 / want)
+    assert (np.abs(got - want) <= bound).all(), (got, want)
+    # the monitored run is the plain streamed run, bit for bit
+    W2, H2 = dev(W), dev(H)
+    nmf.nmf_mu_ooc(Ah, m, n, k, W2, H2, iters, EPS, batch, budget)
+    np.testing.assert_array_equal(host(Wd), host(W2))
+    np.testing.assert_array_equal(host(Hd), host(H2))
+
+
+def test_ooc_monitor_argument_errors():
+    A, W, H = case(64, 48, 70, 3)
+    Ah = torch.from_numpy(A).pin_memory()
+    with pytest.raises(nmf.NmfError) as e:
+        nmf.nmf_mu_ooc_monitor(Ah, 64, 48, 70, dev(W), dev(H), 1, EPS, 16, 1 << 20)
+    assert e.value.status == nmf.NMF_EUNSUPPORTED
+
+
 def test_ooc_equals_small_plan_dense_bitwise_when_one_batch():
     """With one batch the out-of-memory path launches the same kernels as the
     resident path without the transposed copy of A (forced here by a caller
