@@ -286,6 +286,33 @@ def test_split_planes_encoding_is_exact(rows, k):
     np.testing.assert_array_equal(total.transpose(0, 2, 1).reshape(groups * 8, KP), Xp.astype(np.float64))
 
 
+def random_shapes(count, seed):
+    """Seeded shapes that mix the kernels' paths: row counts around the 16-row step and the
+    32-row tile, column counts around the 64-, 128- and 256-column slabs (half of them
+    multiples of 4, which the aligned kernels need), ranks around 32 and 64."""
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        m = int(r.choice([r.integers(1, 40), r.integers(40, 700), 16 * r.integers(1, 40) + r.integers(-1, 2)]))
+        n = int(r.choice([r.integers(1, 40), r.integers(40, 700), 64 * r.integers(1, 11) + r.integers(-1, 2)]))
+        if r.random() < 0.5:
+            n = max(4, n // 4 * 4)
+        k = int(r.choice([r.integers(1, 65), r.choice([1, 15, 16, 17, 31, 32, 33, 48, 63, 64])]))
+        out.append((max(m, 1), max(n, 1), k))
+    return out
+
+
+@pytest.mark.parametrize("m,n,k", random_shapes(40, 2024))
+def test_dense_random_shapes_two_iterations(m, n, k):
+    A, W, H = case(m, n, k, 1000 + m + 7 * n + 13 * k)
+    Wg, Hg = run_dense(A, W, H, 2)
+    Wr, Hr = orc.mu_dense(A, W, H, 2, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 2 * TOL1)
+    got = nmf.nmf_residual_dense(dev(A), m, n, k, dev(W), dev(H))
+    want = orc.residual_dense(A, W, H)
+    assert abs(got - want) <= 1e-5 * want
+
+
 # ---- objective and tolerance-driven run --------------------------------------------
 
 # the last six take the streaming kernel: whole 32-row tiles (with up to 31 rows left to the
