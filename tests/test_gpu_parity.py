@@ -481,6 +481,40 @@ def test_ooc_pageable_host_memory_and_config1():
     check(host(Wd), host(Hd), Wr, Hr, TOLN)
 
 
+def random_ooc_cases(count, seed):
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        m = int(r.integers(1, 900))
+        n = int(r.choice([r.integers(1, 600), 4 * r.integers(1, 150)]))
+        k = int(r.choice([r.integers(1, 65), r.integers(65, 140), r.choice([16, 32, 64])]))
+        batch = int(r.choice([1, r.integers(1, m + 1), r.integers(1, m + 1), m, m + 5]))
+        out.append((m, n, k, batch, int(r.integers(1, 4))))
+    return out
+
+
+@pytest.mark.parametrize("m,n,k,batch,slots", random_ooc_cases(16, 2026))
+def test_ooc_random_cases_two_iterations(m, n, k, batch, slots):
+    """Streamed dense runs with W on the device and with W in host memory, any batch size,
+    against the oracle; for ranks up to 64 also the objective of both iterations."""
+    A, W, H = case(m, n, k, 2000 + m + n + k)
+    eps = float(np.float32(EPS))
+    Wr, Hr = orc.mu_dense(A, W, H, 2, eps)
+    Ah = torch.from_numpy(A).pin_memory()
+    budget = slots * (((min(batch, m) * n * 4) + 255) // 256 * 256)
+    Wd, Hd = dev(W), dev(H)
+    if k <= 64:
+        got = nmf.nmf_mu_ooc_monitor(Ah, m, n, k, Wd, Hd, 2, EPS, batch, budget)
+        want = orc.residual_dense(A, Wr, Hr)
+        normA2 = float(np.sum(A.astype(np.float64) ** 2))
+        assert abs(got[1] - want) <= 1e-5 * want + 3e-7 * normA2 / want
+    else:
+        nmf.nmf_mu_ooc(Ah, m, n, k, Wd, Hd, 2, EPS, batch, budget)
+    check(host(Wd), host(Hd), Wr, Hr, 2 * TOL1 if k <= 64 else 1e-4)
+    Wg, Hg, _ = run_hostw(A, W, H, 2, batch, slots)
+    check(Wg, Hg, Wr, Hr, 1e-4)
+
+
 # ---- ranks above 64 (rank-sliced engine) and the host-resident-W pipeline ---------------
 
 @pytest.mark.parametrize("m,n,k,iters", [(300, 200, 65, 1), (515, 260, 100, 1), (257, 1031, 96, 2),
@@ -815,6 +849,36 @@ def test_csr_empty_matrix():
     assert rc == 0
     assert (host(Wd) == 0).all() and (host(Hd) == 0).all()
     del ci, va
+
+
+def random_csr_cases(count, seed):
+    r = np.random.default_rng(seed)
+    out = []
+    for _ in range(count):
+        m = int(r.choice([r.integers(1, 50), r.integers(50, 3000)]))
+        n = int(r.choice([r.integers(1, 50), r.integers(50, 3000)]))
+        k = int(r.choice([r.integers(1, 65), r.choice([1, 3, 4, 5, 8, 16, 17, 32, 33, 64])]))
+        density = float(r.choice([0.0005, 0.005, 0.05, 0.5]))
+        out.append((m, n, k, density))
+    return out
+
+
+@pytest.mark.parametrize("m,n,k,density", random_csr_cases(16, 2025))
+def test_csr_random_cases_two_iterations_with_objective(m, n, k, density):
+    rowptr, colidx, vals = (t.numpy() for t in nmf_inputs.csr_uniform(m, n, density, seed=m + 3 * n + k))
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=5 * m + n + k))
+    eps = float(np.float32(EPS))
+    Wr, Hr = orc.mu_csr(rowptr, colidx, vals, m, n, W, H, 2, eps)
+    Wd, Hd = dev(W), dev(H)
+    got = nmf.nmf_mu_csr_monitor(dev(rowptr, torch.int64), dev(colidx, torch.int32), dev(vals), m, n, int(vals.size),
+                                 k, Wd, Hd, 2, EPS)
+    check(host(Wd), host(Hd), Wr, Hr, 2 * TOL1)
+    want = orc.residual_csr(rowptr, colidx, vals, m, n, Wr, Hr)
+    normA2 = float(np.sum(vals.astype(np.float64) ** 2))
+    if want > 0:
+        assert abs(got[1] - want) <= 1e-5 * want + 3e-7 * normA2 / want
+    else:
+        assert got[1] == 0.0
 
 
 def csr_monitor_case(rowptr, colidx, vals, m, n, W, H, iters):
