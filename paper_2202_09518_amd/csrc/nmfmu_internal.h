@@ -100,7 +100,7 @@ int gram_w_blocks(int64_t rows);
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
                            const float *GH, float *W, float eps, hipStream_t st, double *dpart = nullptr);
 int64_t aht_pass_blocks(int64_t rows);
-// out[0] = in[0] + ... + in[count - 1], added in index order.
+// out[0] = sum of in[0 .. count), added in a fixed order (strided per thread, then the threads in order).
 hipError_t launch_sum_f64(const double *in, int64_t count, double *out, hipStream_t st);
 
 // out[0] = ||A - W H||_F; partial: residual_partials(m, n) doubles of scratch.
