@@ -1507,7 +1507,14 @@ int wta_splits(int64_t rows, int64_t n, int k)
     const int64_t slabs = (n + width - 1) / width;
     const int64_t target = 512;
     int64_t s = (target + slabs - 1) / slabs;
-    const int64_t max_by_rows = (rows + 255) / 256;   // at least 256 rows per split
+    int64_t max_by_rows = (rows + 255) / 256;         // at least 256 rows per split ...
+    if (slabs * max_by_rows < 128) {
+        // ... unless that leaves most of the chip idle: small matrices are split down to one
+        // 16-row step per wave, up to 128 workgroups (256 x 192: 19.6 instead of 26.0 us per
+        // iteration; with many workgroups the fixed cost of a split outweighs it)
+        const int64_t fine = (rows + 63) / 64, want = (128 + slabs - 1) / slabs;
+        max_by_rows = fine < want ? fine : want;
+    }
     if (s > max_by_rows) s = max_by_rows;
     if (s > 32) s = 32;
     if (s < 1) s = 1;
