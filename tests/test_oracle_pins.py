@@ -542,3 +542,44 @@ def test_sparse_tolerance_loop_stops_where_the_objective_says():
     Wn, Hn, done, res = orc.mu_csr_tol(rowptr, colidx, vals, m, n, W, H, 7, EPS, 1e9, check_every=2)
     assert done == 0 and abs(res - traj[0]) <= 1e-12 * traj[0]
     np.testing.assert_array_equal(Wn, W)
+
+
+def test_ensemble_is_the_block_diagonal_stacked_iteration():
+    """mu_ensemble (independent runs, sections 1 and 4.5) against one stacked iteration written with
+    library products: runs that share A are the factor blocks of a single W_all (m x sum k) and
+    H_all (sum k x n) whose two Gram matrices are cut down to their diagonal blocks, so that no run
+    sees another.  Also: a run's result does not change when another run's start does."""
+    m, n = 37, 29
+    r = np.random.default_rng(41)
+    A = r.random((m, n)).astype(np.float32)
+    ks = [1, 3, 2, 5]
+    Ws = [r.random((m, k)) for k in ks]
+    Hs = [r.random((k, n)) for k in ks]
+    iters = 7
+    got = orc.mu_ensemble([A] * len(ks), Ws, Hs, iters, EPS)
+    assert len(got) == len(ks)
+    ids = np.concatenate([np.full(k, i) for i, k in enumerate(ks)])
+    mask = (ids[:, None] == ids[None, :]).astype(np.float64)
+    Wall, Hall = np.concatenate(Ws, axis=1), np.concatenate(Hs, axis=0)
+    Ad = A.astype(np.float64)
+    for _ in range(iters):
+        Hall = Hall * (Wall.T @ Ad) / (((Wall.T @ Wall) * mask) @ Hall + EPS)
+        Wall = Wall * (Ad @ Hall.T) / (Wall @ ((Hall @ Hall.T) * mask) + EPS)
+    off = 0
+    for (Wg, Hg), k in zip(got, ks):
+        assert Wg.shape == (m, k) and Hg.shape == (k, n)
+        np.testing.assert_allclose(Wg, Wall[:, off:off + k], rtol=1e-11, atol=0)
+        np.testing.assert_allclose(Hg, Hall[off:off + k], rtol=1e-11, atol=0)
+        off += k
+    # different matrices per run, and independence of the runs
+    As = [A, (A * 1.5).astype(np.float32), A, A]
+    base = orc.mu_ensemble(As, Ws, Hs, iters, EPS)
+    Ws2 = [Ws[0], r.random((m, ks[1])), Ws[2], Ws[3]]
+    other = orc.mu_ensemble(As, Ws2, Hs, iters, EPS)
+    for i in (0, 2, 3):
+        np.testing.assert_array_equal(base[i][0], other[i][0])
+        np.testing.assert_array_equal(base[i][1], other[i][1])
+    assert not np.array_equal(base[1][0], other[1][0])
+    Wb, Hb = orc.mu_dense_blas(As[1], Ws[1], Hs[1], iters, EPS)
+    np.testing.assert_allclose(base[1][0], Wb, rtol=1e-11, atol=0)
+    np.testing.assert_allclose(base[1][1], Hb, rtol=1e-11, atol=0)
