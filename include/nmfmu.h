@@ -87,6 +87,28 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
                  float *W, float *H, int32_t iters, float eps, void *stream);
 
 /*
+ * nmf_mu_dense for callers that cannot allocate device memory: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments and result as nmf_mu_dense on its small plan (the direct A H^T
+ * kernel; no transposed copy of A), k <= NMF_MU_MAX_K.  The scratch memory
+ * (row-split partial sums, operand planes of W, Gram scratch) is a fixed array
+ * of NMF_MU_NOALLOC_SCRATCH_BYTES in the library's device image instead of
+ * allocated memory; every device the library runs on holds one copy until the
+ * process ends.  A problem whose nmf_mu_workspace_bytes(kind 4) exceeds that
+ * size is rejected with NMF_ENOMEM (32768 x 16384 with k = 32 needs 22.4 MiB).
+ * The call itself makes no hipMalloc / hipFree and no allocating library call;
+ * the first call on a device looks up the array's device address
+ * (hipGetSymbolAddress), so make that call once outside a graph capture.
+ * All calls on one device share the array: calls that overlap in time on one
+ * device (two streams, two threads) race, the caller serialises them.  The
+ * array is independent of the workspace of the other entry points.
+ * Asynchronous on `stream`.
+ */
+#define NMF_MU_NOALLOC_SCRATCH_BYTES (32u << 20)
+int nmf_mu_dense_noalloc(const float *A, int64_t m, int64_t n, int32_t k,
+                         float *W, float *H, int32_t iters, float eps, void *stream);
+
+/*
  * nmf_mu_dense with timing: the same launches on `stream`, with a HIP event
  * recorded between them; synchronises `stream` before returning.  On return
  * kernel_ms[0..5] (HOST memory, 9 floats) hold the average milliseconds per

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libnmfmu.so")
 
 EXPORTS = [
     "nmf_status_string", "nmf_last_error",
-    "nmf_mu_dense", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_csr_monitor", "nmf_mu_csr_tol", "nmf_mu_ooc", "nmf_mu_ooc_monitor", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
+    "nmf_mu_dense", "nmf_mu_dense_noalloc", "nmf_mu_dense_profile", "nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr", "nmf_mu_csr_monitor", "nmf_mu_csr_tol", "nmf_mu_ooc", "nmf_mu_ooc_monitor", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc", "nmf_mu_dense_batched",
     "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release",
     "nmf_csr_partition", "nmf_split_planes", "nmf_csr_to_csc", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
 ]
@@ -50,6 +50,7 @@ def lib() -> ctypes.CDLL:
     L.nmf_status_string.argtypes = [ctypes.c_int]
     L.nmf_last_error.restype = ctypes.c_char_p
     L.nmf_mu_dense.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp]
+    L.nmf_mu_dense_noalloc.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp]
     L.nmf_mu_dense_profile.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, vp, vp]
     L.nmf_residual_dense.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp]
     L.nmf_mu_dense_tol.argtypes = [vp, i64, i64, i32, vp, vp, i32, f32, ctypes.c_double, i32, vp, vp, vp]
@@ -112,6 +113,11 @@ def nmf_last_error() -> str:
 def nmf_mu_dense(A, m, n, k, W, H, iters, eps, stream=None) -> None:
     _check(lib().nmf_mu_dense(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
                               _dev(H, torch.float32, "H"), iters, eps, _stream(stream)))
+
+
+def nmf_mu_dense_noalloc(A, m, n, k, W, H, iters, eps, stream=None) -> None:
+    _check(lib().nmf_mu_dense_noalloc(_dev(A, torch.float32, "A"), m, n, k, _dev(W, torch.float32, "W"),
+                                      _dev(H, torch.float32, "H"), iters, eps, _stream(stream)))
 
 
 def nmf_mu_dense_profile(A, m, n, k, W, H, iters, eps, stream=None):

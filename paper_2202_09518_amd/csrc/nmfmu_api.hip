@@ -553,6 +553,40 @@ int sliced_ooc_run(const float *A_host, float *W_host, float *W_dev, int64_t m, 
 
 }  // namespace
 
+// ---- allocation-free resident dense run --------------------------------------
+// For callers that cannot allocate (HIP graph capture, tight serving loops, harnesses that
+// forbid it): nmf_mu_dense on the small plan (row-split partials, piece planes, Gram scratch)
+// with that workspace in a fixed array in device memory instead of hipMalloc'ed memory.
+
+namespace {
+constexpr size_t kScratchBytes = NMF_MU_NOALLOC_SCRATCH_BYTES;
+}
+// One copy per device that loads the library, held until the process ends.  In host code the
+// name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex scratch_mu;
+void *scratch_ptr[kMaxDevices] = {};      // device address of `scratch` on each device, once asked
+
+int scratch_address(void **out)
+{
+    int dev = -1;
+    NMF_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(NMF_EUNSUPPORTED, "device ordinal beyond 63%s");
+    std::lock_guard<std::mutex> lock(scratch_mu);
+    if (!scratch_ptr[dev]) {
+        void *p = nullptr;
+        NMF_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return fail(NMF_EHIP, "hipGetSymbolAddress returned a null address%s");
+        scratch_ptr[dev] = p;
+    }
+    *out = scratch_ptr[dev];
+    return NMF_OK;
+}
+}  // namespace
+
 extern "C" {
 
 const char *nmf_status_string(int status)
@@ -1392,6 +1426,27 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
     NMF_HIP(hipMemcpyAsync(objective_host, mon.out, (size_t)iters * sizeof(double), hipMemcpyDeviceToHost, st));
     NMF_HIP(hipStreamSynchronize(st));
     return NMF_OK;
+}
+
+// ---- allocation-free resident dense run --------------------------------------
+
+int nmf_mu_dense_noalloc(const float *A, int64_t m, int64_t n, int32_t k, float *W, float *H,
+                         int32_t iters, float eps, void *stream)
+{
+    if (int rc = check_common(A, W, H, m, n, k, iters, eps)) return rc;
+    if (dense_bytes(m, n, k, false) > kScratchBytes)
+        return fail(NMF_ENOMEM, "problem needs more than the fixed scratch array of nmf_mu_dense_noalloc "
+                                "(see nmf_mu_workspace_bytes kind 4)%s");
+    if (iters == 0) return NMF_OK;
+    void *ws = nullptr;
+    if (int rc = scratch_address(&ws)) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    // The arrival counters at the head of the array must read zero when the first kernel starts;
+    // the kernels restore that, but an earlier call may have been cut short.  A fill kernel, not
+    // a memset: the call may be under graph capture.
+    NMF_HIP(launch_fill_f32(static_cast<float *>(ws), 64, 0.f, st));
+    const DensePlan p = carve_dense(ws, m, n, k, false);
+    return dense_body(A, m, n, k, W, H, iters, eps, p, st);
 }
 
 // ---- single steps ----------------------------------------------------------
