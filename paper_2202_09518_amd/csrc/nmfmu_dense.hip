@@ -88,6 +88,13 @@ __device__ __forceinline__ int acc_row(int v, int half) { return (v & 3) + 4 * h
 // lane index is flipped by 8 q so that the epilogue, which walks columns 4 jj + q, reads
 // 32 different banks.
 constexpr int kFlushSteps = 32;
+
+// Cache policy of the buffer loads that stream A: the non-temporal bit.  Every element of A is
+// used once per pass, so its lines are marked for early eviction and leave the L2 and the
+// Infinity Cache to the operands that are re-read (the piece planes, the partial results).
+// Measured on a bare read of 32768 x 16384 floats in the pass's launch shape: 0.313 ms
+// (6.85 TB/s) against 0.345 ms (6.22 TB/s) with the default policy.
+constexpr int kStreamLoad = 2;
 constexpr int kTotFloats = 64 * 64;
 __device__ __forceinline__ int tot_slot(int q, int v, int lane) { return (q * 16 + v) * 64 + (lane ^ (8 * q)); }
 
@@ -574,7 +581,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
         const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<u32x4 *>(planes + (ng ? g : 0) * 3 * 32), 0, (int)(ng * 3 * 32 * 16), kRsrcFlags);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b128(ra, loff + r * rowb, 0, 0);
+        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b128(ra, loff + r * rowb, 0, kStreamLoad);
 #pragma unroll
         for (int pl = 0; pl < 3; ++pl) s.wt[pl] = __builtin_amdgcn_raw_buffer_load_b128(rp, poff + pl * 32 * 16, 0, 0);
     };
@@ -699,7 +706,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kerne
         const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<u32x4 *>(planes + (ng ? g : 0) * 3 * KP), 0, (int)(ng * 3 * KP * 16), kRsrcFlags);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b64(ra, loff + r * rowb, 0, 0);
+        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b64(ra, loff + r * rowb, 0, kStreamLoad);
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
