@@ -87,7 +87,8 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
     names = ["gram_w", "wta_pass", "h_update", "gram_h", "aht_pass", "w_update"]
     kms = nmf.nmf_mu_dense_profile(A, m, n, k, W, H, min(args.steps, 50), EPS)
     kern = dict(zip(names, kms[:6]))
-    log("[bench] plan:", "mirrored (A and A^T resident)" if kms[6] else "direct")
+    plan = {0: "small (direct A H^T kernel)", 1: "mirrored (A and A^T resident)", 2: "row plan (both passes stream the row-major A)"}[int(kms[6])]
+    log("[bench] plan:", plan)
     log("[bench] per-kernel ms:", {a: round(b, 4) for a, b in kern.items()})
     # the two pass kernels alone: 20 launches back to back between two HIP events on their
     # stream (the per-kernel figures above carry the event commands around every launch)
@@ -103,7 +104,7 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{tag}: dense fp32 A {m}x{n} resident, planted rank {rank} x U[0.95,1.05), k={k}, "
-                               "one step = one MU iteration (2 reads of A)", "m": m, "n": n, "k": k},
+                               "one step = one MU iteration (2 reads of A)", "m": m, "n": n, "k": k, "plan": plan},
         "gbs_over_A": gbs_iter, "frac_hbm_peak_over_A": gbs_iter / HBM_PEAK_GBS,
         "tflops_paper_model": flops_per_iteration(m, n, k) / (ms_step * 1e-3) / 1e12,
         "kernel_ms": kern, "pass_kernel_ms_back_to_back": alone,

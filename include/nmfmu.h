@@ -95,7 +95,7 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
  * of NMF_MU_NOALLOC_SCRATCH_BYTES in the library's device image instead of
  * allocated memory; every device the library runs on holds one copy until the
  * process ends.  A problem whose nmf_mu_workspace_bytes(kind 4) exceeds that
- * size is rejected with NMF_ENOMEM (32768 x 16384 with k = 32 needs 22.4 MiB).
+ * size is rejected with NMF_ENOMEM (32768 x 16384 with k = 32 needs 28.4 MiB).
  * The call itself makes no hipMalloc / hipFree and no allocating library call;
  * the first call on a device looks up the array's device address
  * (hipGetSymbolAddress), so make that call once outside a graph capture.
@@ -116,11 +116,14 @@ int nmf_mu_dense_noalloc(const float *A, int64_t m, int64_t n, int32_t k,
  *   [0] W^T W   [1] W^T A pass   [2] H update   [3] H H^T
  *   [4] A H^T pass (on the mirrored copy A^T, or the direct kernel with the W
  *       update fused)   [5] W update (0 for the direct kernel)
- * and kernel_ms[6] is 1 if the mirrored plan ran (see nmf_mu_workspace_bytes),
- * else 0.  kernel_ms[7] and [8]: milliseconds per launch of the W^T A pass and
- * (mirrored plan only, else 0) of the pass on A^T, from 20 launches back to
- * back between two events after the run, i.e. without the event commands that
- * surround every kernel in [0..5].  1 <= iters <= 4096.
+ * and kernel_ms[6] names the plan that ran: 2 the row plan (k <= 32, aligned A:
+ * both passes stream the row-major A, [0], [3] and [5] are 0 because the Gram
+ * matrices and the W update are by-products of the other three kernels), 1 the
+ * mirrored plan (see nmf_mu_workspace_bytes), 0 the small plan.  kernel_ms[7] and
+ * [8]: milliseconds per launch of the W^T A pass and (plans 1 and 2, else 0) of
+ * the A H^T pass, from 20 launches back to back between two events after the
+ * run, i.e. without the event commands that surround every kernel in [0..5].
+ * 1 <= iters <= 4096.
  */
 int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k,
                          float *W, float *H, int32_t iters, float eps, void *stream,

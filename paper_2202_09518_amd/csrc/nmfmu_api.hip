@@ -141,6 +141,7 @@ struct DensePlan {
     Common c;
     float *ppart;              // row-split partials of either pass
     void *planes;              // bf16 piece planes of the factor a pass contracts with
+    void *planes2;             // row plan: piece planes of H^T (planes then holds those of W)
     float *At, *Wt, *Ht;       // mirrored only
     int s1, s2;                // row splits of the pass over A / over A^T
     int64_t rps1, rps2;
@@ -150,7 +151,7 @@ size_t dense_bytes(int64_t m, int64_t n, int k, bool mirrored)
 {
     const size_t p1 = (size_t)wta_splits_bound(m, n, k) * k * n, p2 = (size_t)wta_splits_bound(n, m, k) * k * m;
     size_t b = common_bytes(k) + align_up(((mirrored && p2 > p1) ? p2 : p1) * sizeof(float)) +
-               align_up(planes_bytes((mirrored && n > m) ? n : m));
+               align_up(planes_bytes((mirrored && n > m) ? n : m)) + align_up(planes_bytes(n));
     if (mirrored)
         b += align_up((size_t)m * n * sizeof(float)) + align_up((size_t)k * m * sizeof(float)) +
              align_up((size_t)n * k * sizeof(float));
@@ -170,6 +171,7 @@ DensePlan carve_dense(void *ws, int64_t m, int64_t n, int k, bool mirrored)
     const size_t p1 = (size_t)wta_splits_bound(m, n, k) * k * n, p2 = (size_t)wta_splits_bound(n, m, k) * k * m;
     p.ppart = cv.take<float>((mirrored && p2 > p1) ? p2 : p1);
     p.planes = cv.take<char>(planes_bytes((mirrored && n > m) ? n : m));
+    p.planes2 = cv.take<char>(planes_bytes(n));
     p.At = p.Wt = p.Ht = nullptr;
     if (mirrored) {
         p.At = cv.take<float>((size_t)m * n);
@@ -180,9 +182,13 @@ DensePlan carve_dense(void *ws, int64_t m, int64_t n, int k, bool mirrored)
 }
 
 // Workspace for a dense run: the mirrored plan if it can be had, else the small one.
-int dense_workspace(int64_t m, int64_t n, int k, void **ws, bool *mirrored)
+int dense_workspace(const float *A, int64_t m, int64_t n, int k, void **ws, bool *mirrored)
 {
     const size_t big = dense_bytes(m, n, k, true), small = dense_bytes(m, n, k, false);
+    if (aht_rows_ok(A, m, n, k)) {     // the row plan streams A itself for both products
+        *mirrored = false;
+        return ensure_workspace(small, ws);
+    }
     if (g.ws && g.ws_bytes >= big) {
         *ws = g.ws;
         *mirrored = true;
@@ -221,6 +227,37 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
     // counts follow the rank actually run; the partial buffer holds the largest case.
     const int s1 = wta_splits(m, n, k), s2 = wta_splits(n, m, k);
     const int64_t rps1 = wta_rows_per_split(m, s1), rps2 = wta_rows_per_split(n, s2);
+    if (aht_rows_ok(A, m, n, k)) {
+        // Row plan (k <= 32): both products stream the row-major A.  The W^T A pass reads the piece
+        // planes of W and, on the side, adds the tile sets of W^T W up in groups; the H update writes
+        // the planes of H^T and the tile sets of H H^T, which a small launch adds up; the A H^T pass
+        // with the fused W update writes the planes of the new W and the tile sets of its W^T W.
+        const int nbw = aht_rows_blocks(m), nbh = factor_update_blocks(n);
+        const int ngw = gram_groups(nbw);
+        // planes and W^T W of the W handed in, with the summation order of an updating launch
+        NMF_HIP(launch_aht_rows(nullptr, m, n, k, nullptr, nullptr, W, p.planes, c.gwp, eps, st, true));
+        if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+        for (int it = 0; it < iters; ++it) {
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_wta_pass(A, m, n, k, W, p.planes, true, p.ppart, s1, rps1, false, st, c.gwp, nbw, c.gws));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_factor_update(H, nullptr, p.ppart, s1, nullptr, c.gws, ngw, c.ghp, k, n, eps, st, map, p.planes2));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            NMF_HIP(launch_gram_sum(c.ghp, nbh, k, c.gh, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            const bool report = mon && (!mon->last_only || it == iters - 1);
+            NMF_HIP(launch_aht_rows(A, m, n, k, p.planes2, c.gh, W, p.planes, c.gwp, eps, st, false, map,
+                                    report ? mon->dpart : nullptr));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            if (ev) NMF_HIP(hipEventRecord(*ev++, st));
+            if (report) {
+                NMF_HIP(launch_gram_sum(c.gwp, nbw, k, c.gw, st));
+                NMF_HIP(launch_objective(mon->dpart, nbw, c.gw, c.gh, k, mon->normA2,
+                                         mon->out + (mon->last_only ? 0 : it), st));
+            }
+        }
+        return NMF_OK;
+    }
     if (p.mirrored) {
         if (!a_is_mirrored) NMF_HIP(launch_transpose(A, m, n, p.At, st));
         NMF_HIP(launch_transpose(W, m, k, p.Wt, st));
@@ -699,7 +736,7 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k, float *W, floa
         return sliced_dense_body(A, m, n, k, W, H, iters, eps, p, static_cast<hipStream_t>(stream));
     }
     bool mirrored = false;
-    if (int rc = dense_workspace(m, n, k, &ws, &mirrored)) return rc;
+    if (int rc = dense_workspace(A, m, n, k, &ws, &mirrored)) return rc;
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
     return dense_body(A, m, n, k, W, H, iters, eps, p, static_cast<hipStream_t>(stream));
 }
@@ -714,7 +751,7 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float 
     std::lock_guard<std::mutex> lock(g.mu);
     void *ws = nullptr;
     bool mirrored = false;
-    if (int rc = dense_workspace(m, n, k, &ws, &mirrored)) return rc;
+    if (int rc = dense_workspace(A, m, n, k, &ws, &mirrored)) return rc;
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
     constexpr int NK = kDenseKernels;
     std::vector<hipEvent_t> ev((size_t)iters * NK + 1, nullptr);
@@ -735,7 +772,7 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float 
                 sum[j] += ms;
             }
         for (int j = 0; j < NK; ++j) kernel_ms[j] = (float)(sum[j] / iters);
-        kernel_ms[NK] = mirrored ? 1.f : 0.f;
+        kernel_ms[NK] = aht_rows_ok(A, m, n, k) ? 2.f : (mirrored ? 1.f : 0.f);
         kernel_ms[NK + 1] = kernel_ms[NK + 2] = 0.f;
     }
     // The pass kernels once more, `reps` launches back to back between two events: the
@@ -745,13 +782,18 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float 
         const int reps = 20;
         const int s1 = wta_splits(m, n, k), s2 = wta_splits(n, m, k);
         const int64_t rps1 = wta_rows_per_split(m, s1), rps2 = wta_rows_per_split(n, s2);
-        for (int which = 0; which < (mirrored ? 2 : 1) && rc == NMF_OK; ++which) {
+        const bool rows_plan = aht_rows_ok(A, m, n, k);
+        const Common &c = p.c;
+        for (int which = 0; which < ((mirrored || rows_plan) ? 2 : 1) && rc == NMF_OK; ++which) {
             if (which == 0) (void)launch_split_planes(W, m, k, p.planes, st);
-            else (void)launch_split_planes(p.Ht, n, k, p.planes, st);
+            else if (!rows_plan) (void)launch_split_planes(p.Ht, n, k, p.planes, st);
             hipError_t e = hipEventRecord(ev[0], st);
             for (int r = 0; r < reps && e == hipSuccess; ++r)
                 e = which == 0 ? launch_wta_pass(A, m, n, k, W, p.planes, true, p.ppart, s1, rps1, false, st)
-                               : launch_wta_pass(p.At, n, m, k, p.Ht, p.planes, true, p.ppart, s2, rps2, false, st);
+                    : rows_plan  // the fused pass without its stores to W
+                        ? launch_aht_rows(A, m, n, k, p.planes2, c.gh, W, p.planes, c.gwp, eps, st, false, nullptr,
+                                          nullptr, true)
+                        : launch_wta_pass(p.At, n, m, k, p.Ht, p.planes, true, p.ppart, s2, rps2, false, st);
             if (e == hipSuccess) e = hipEventRecord(ev[1], st);
             if (e == hipSuccess) e = hipEventSynchronize(ev[1]);
             float ms = 0.f;
@@ -805,7 +847,7 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
     if (!can_stack) {
         (void)hipGetLastError();
         bool mirrored = false;
-        if (int rc = dense_workspace(m, n, kmax, &ws, &mirrored)) return rc;
+        if (int rc = dense_workspace(nullptr, m, n, kmax, &ws, &mirrored)) return rc;
         const DensePlan p1 = carve_dense(ws, m, n, kmax, mirrored);
         for (int r = 0; r < n_runs; ++r) {
             const bool same_a = r > 0 && A[r] == A[r - 1];
@@ -1335,13 +1377,15 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     const size_t extra = residual_scratch_bytes(m, n) + align_up((size_t)kFinMaxBlocks * sizeof(double)) +
                          align_up(4097 * sizeof(double)) + kAlign;
     const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
-    if ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK)) {
+    const bool rows_plan = aht_rows_ok(A, m, n, k);
+    if (!rows_plan && ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK))) {
         mirrored = true;
     } else {
         (void)hipGetLastError();
         if (int rc = ensure_workspace(small, &ws)) return rc;
     }
     ws = g.ws;
+    const bool fast = mirrored || rows_plan;   // plans whose W update leaves the objective's terms behind
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
     Carve cv(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
     double *scratch = cv.take<double>((size_t)residual_partials(m, n) + 1);
@@ -1356,7 +1400,7 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     bool exact = true;       // `res` comes from the tiled evaluation (not from the expansion)
     if (int rc = residual_to_host(A, m, n, k, W, H, scratch, &res, st)) return rc;
     double normA2 = 0.0;
-    if (mirrored && max_iters > 0 && res > tol) {
+    if (fast && max_iters > 0 && res > tol) {
         NMF_HIP(launch_sumsq(A, m * n, mon.normA2 + 1, mon.normA2, st));
         NMF_HIP(hipMemcpyAsync(&normA2, mon.normA2, sizeof(double), hipMemcpyDeviceToHost, st));
         NMF_HIP(hipStreamSynchronize(st));
@@ -1364,11 +1408,11 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     bool have_at = false;
     while (done < max_iters && res > tol) {
         const int chunk = (max_iters - done < check_every) ? max_iters - done : check_every;
-        if (int rc = dense_body(A, m, n, k, W, H, chunk, eps, p, st, have_at, nullptr, nullptr, mirrored ? &mon : nullptr))
+        if (int rc = dense_body(A, m, n, k, W, H, chunk, eps, p, st, have_at, nullptr, nullptr, fast ? &mon : nullptr))
             return rc;
         have_at = mirrored;
         done += chunk;
-        if (mirrored) {
+        if (fast) {
             // The objective of the chunk's last iteration from the by-products of its W update
             // (no pass over A); its error is bounded by the fp32 sums of its three terms.  Only
             // when it comes within that bound of the tolerance is the exact value needed.
@@ -1406,7 +1450,8 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
     const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
     void *ws = nullptr;
     bool mirrored = false;
-    if ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK)) {
+    const bool rows_plan = aht_rows_ok(A, m, n, k);
+    if (!rows_plan && ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK))) {
         mirrored = true;
     } else {
         (void)hipGetLastError();
@@ -1421,7 +1466,7 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
     mon.out = cv.take<double>((size_t)iters);
     mon.res = cv.take<double>((size_t)residual_partials(m, n) + 1);
     mon.last_only = false;
-    if (mirrored) NMF_HIP(launch_sumsq(A, m * n, mon.normA2 + 1, mon.normA2, st));
+    if (mirrored || rows_plan) NMF_HIP(launch_sumsq(A, m * n, mon.normA2 + 1, mon.normA2, st));
     if (int rc = dense_body(A, m, n, k, W, H, iters, eps, p, st, false, nullptr, nullptr, &mon)) return rc;
     NMF_HIP(hipMemcpyAsync(objective_host, mon.out, (size_t)iters * sizeof(double), hipMemcpyDeviceToHost, st));
     NMF_HIP(hipStreamSynchronize(st));

@@ -1156,6 +1156,291 @@ __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__
     }
 }
 
+// ---------------------------------------------------------------------------
+// A H^T pass on the row-major A with the W update fused, k <= 32 ("row plan"; 16-byte aligned
+// A, n % 4 == 0, n < 2^24).  A workgroup of 8 waves owns 64 RG rows of A and W at a time
+// (row blocks blockIdx.x, + gridDim.x, ...): RG row groups of 64 rows, 8 / RG waves per
+// group, which split the 64-column chunks of the block between them; a wave's sub-tile is
+// 32 rows x 64 columns, two per chunk.  MFMA roles: A_op = A elements (32 rows x 16 columns,
+// a lane holds 8 consecutive columns of one row, cut into bf16 pieces in registers), B_op =
+// the piece planes of H^T (16 columns x 32 factors: the planes the H update writes for its
+// new H), so the sums are the exact-piece sums of the W^T A pass, and like there a matrix
+// accumulator runs for at most 32 products deep (8 chunks) before it is added, in rounded
+// fp32, to the wave's totals.  An operand layout with lanes down the rows would make every
+// lane of a load touch its own cache line, so A is loaded coalesced (a wave instruction =
+// 4 rows x 256 contiguous bytes, non-temporal) and turned through a wave-private 8 KiB tile
+// of LDS (16-byte chunks swizzled by row, conflict free both ways; no barrier: only the
+// wave itself touches its tile).  The planes of a chunk (48 registers) serve both row
+// tiles.  Every row block starts its walk over the columns at another chunk (17 x block
+// index): launched in step on the same columns, the workgroups would crowd the same memory
+// channels (0.338 against 0.318 ms for the bare loads on 32768 x 16384).
+//
+// Epilogue per row block: the sums of a row group's waves are added through LDS in wave
+// order; W <- W * Q / (W GH + eps) for the block's rows with GH = H H^T (k x k, complete);
+// then from the new rows in LDS: their bf16 piece planes (operand of the next W^T A pass),
+// this workgroup's share of W^T W (fp32 matrix instruction, one tile set per workgroup in
+// gout, which the next W^T A pass adds up in groups) and, with dpart, its share of
+// <A H^T, W_new> in double.
+// mode 1: no pass and no update, only the planes and the Gram share of W as it is (the
+// same summation order, so that a run cut into two calls gives the same bits).  mode 2: the
+// whole pass with the stores to W and its planes left out (timing).
+// ---------------------------------------------------------------------------
+template <int RG>
+__global__ __launch_bounds__(512, 2) void aht_rows_kernel(
+    const float *__restrict__ A, const u32x4 *__restrict__ planesH, const float *__restrict__ GH,
+    float *W, u32x4 *__restrict__ planesW, float *__restrict__ gout,
+    double *__restrict__ dpart, int64_t rows, int64_t n, int k, float eps, int mode, BlockMap bm)
+{
+    constexpr int NW = 8, NWC = NW / RG, RB = 64 * RG, LDW = 33;
+    constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+    __shared__ float lds[NW * 2048];          // all of the 64 KiB a workgroup can have
+    double *dsum = reinterpret_cast<double *>(lds + 16368);      // used after the last row block only
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int rg = w / NWC, wc = w % NWC;
+    float *stg = lds + w * 2048;
+    const int jj = lane & 31, half = lane >> 5;
+    const unsigned rowb = (unsigned)(n * 4);
+    const int64_t nchunks = (n + 63) >> 6;
+    const int64_t ngroups = (n + 7) >> 3;
+    const int64_t nblocks = (rows + RB - 1) / RB;
+    // coalesced loads: instruction u of a sub-tile covers rows 4u .. 4u+3, lane = (row, 16-byte chunk)
+    const int lrow = lane >> 4, lch = lane & 15;
+    const unsigned loff = (unsigned)lrow * rowb + (unsigned)lch * 16;
+
+    // epilogue arrays (they alias the staging tiles; barriers separate the phases): the sums of
+    // row group g in accumulator layout at lds + g * NWC * 2048 + (rt * 16 + v) * 64 + lane
+    float *Ws = lds + 2048;               // old rows   [RB][LDW]
+    float *Gs = Ws + 128 * LDW;           // H H^T      [32][LDW]
+    float *Wn = lds + 10240;              // new rows   [RB][LDW]
+
+    f32x16 gacc = {0};                    // this wave's share of W^T W over all row blocks
+    double dacc = 0.0;
+
+    for (int64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
+        const int64_t i0 = blk * RB;
+        if (mode != 1) {
+            const int64_t rot = (blk * 17) % nchunks;
+            const int64_t ib = i0 + 64 * rg;            // first row of this wave's row group
+            f32x16 acc[2], tot[2];
+#pragma unroll
+            for (int r = 0; r < 2; ++r) acc[r] = tot[r] = f32x16{0};
+            struct Stage {
+                u32x4 a[8];
+            };
+            auto phys = [&](int64_t ch) {
+                const int64_t c = ch + rot;
+                return c >= nchunks ? c - nchunks : c;
+            };
+            auto load_stage = [&](Stage &s, int64_t chl, int rt) {
+                const int64_t rbase = ib + 32 * rt;
+                int64_t av = rows - rbase;                  // rows of this sub-tile that exist
+                av = av < 0 ? 0 : (av > 32 ? 32 : av);
+                if (chl >= nchunks) av = 0;                 // past the last chunk: nothing is loaded
+                const int64_t ch = av ? phys(chl) : 0;
+                const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<float *>(A + (av ? rbase * n + ch * 64 : 0)), 0,
+                    (int)(av ? av * (int64_t)rowb - ch * 256 : 0), kRsrcFlags);
+                // columns at or past n (last chunk only): the lane's offset is pushed out of range
+                const unsigned lo = (ch * 64 + lch * 4 < n) ? loff : 0x7fffffffu;
+#pragma unroll
+                for (int u = 0; u < 8; ++u)
+                    s.a[u] = __builtin_amdgcn_raw_buffer_load_b128(ra, lo + (unsigned)(4 * u) * rowb, 0, kStreamLoad);
+            };
+            u32x4 bp[4][3];
+            auto load_b = [&](int64_t chl) {
+                const int64_t g = phys(chl) * 8;
+                int64_t ng = ngroups - g;                   // 8-column groups of planes that exist
+                ng = ng < 0 ? 0 : (ng > 8 ? 8 : ng);
+                const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
+                    const_cast<u32x4 *>(planesH + (ng ? g : 0) * 3 * 32), 0, (int)(ng * 3 * 32 * 16), kRsrcFlags);
+#pragma unroll
+                for (int s = 0; s < 4; ++s)
+#pragma unroll
+                    for (int pl = 0; pl < 3; ++pl)
+                        bp[s][pl] = __builtin_amdgcn_raw_buffer_load_b128(
+                            rp, (unsigned)((((2 * s + half) * 3 + pl) * 32 + jj) * 16), 0, 0);
+            };
+            auto to_lds = [&](const Stage &s) {
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int row = 4 * u + lrow;
+                    *reinterpret_cast<f32x4 *>(stg + row * 64 + ((lch ^ (row & 15)) << 2)) = __builtin_bit_cast(f32x4, s.a[u]);
+                }
+            };
+            auto compute = [&](f32x16 &a) {
+#pragma unroll
+                for (int s = 0; s < 4; ++s) {
+                    const int c0 = 4 * s + 2 * half;
+                    const f32x4 x0 = *reinterpret_cast<const f32x4 *>(stg + jj * 64 + ((c0 ^ (jj & 15)) << 2));
+                    const f32x4 x1 = *reinterpret_cast<const f32x4 *>(stg + jj * 64 + (((c0 + 1) ^ (jj & 15)) << 2));
+                    u32x4 at[3];
+                    unsigned h0, m0, l0, h1, m1, l1;
+                    split3(x0.x, h0, m0, l0);
+                    split3(x0.y, h1, m1, l1);
+                    at[0][0] = pack2(h0, h1), at[1][0] = pack2(m0, m1), at[2][0] = pack2(l0, l1);
+                    split3(x0.z, h0, m0, l0);
+                    split3(x0.w, h1, m1, l1);
+                    at[0][1] = pack2(h0, h1), at[1][1] = pack2(m0, m1), at[2][1] = pack2(l0, l1);
+                    split3(x1.x, h0, m0, l0);
+                    split3(x1.y, h1, m1, l1);
+                    at[0][2] = pack2(h0, h1), at[1][2] = pack2(m0, m1), at[2][2] = pack2(l0, l1);
+                    split3(x1.z, h0, m0, l0);
+                    split3(x1.w, h1, m1, l1);
+                    at[0][3] = pack2(h0, h1), at[1][3] = pack2(m0, m1), at[2][3] = pack2(l0, l1);
+                    // the nine piece products, smallest first
+                    a = mfma_bf16(at[2], bp[s][2], a);
+                    a = mfma_bf16(at[2], bp[s][1], a);
+                    a = mfma_bf16(at[1], bp[s][2], a);
+                    a = mfma_bf16(at[2], bp[s][0], a);
+                    a = mfma_bf16(at[1], bp[s][1], a);
+                    a = mfma_bf16(at[0], bp[s][2], a);
+                    a = mfma_bf16(at[1], bp[s][0], a);
+                    a = mfma_bf16(at[0], bp[s][1], a);
+                    a = mfma_bf16(at[0], bp[s][0], a);
+                }
+            };
+            // Sub-tiles in the order (chunk, row tile); the loads of the next one are requested
+            // as soon as the current one has gone to LDS.
+            int since = 0;
+            Stage s0;
+            int64_t ch = wc;
+            load_stage(s0, ch, 0);
+            for (; ch < nchunks; ch += NWC) {
+                load_b(ch);
+                to_lds(s0);
+                __builtin_amdgcn_sched_barrier(0);
+                load_stage(s0, ch, 1);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(acc[0]);
+                __builtin_amdgcn_sched_barrier(0);
+                to_lds(s0);
+                __builtin_amdgcn_sched_barrier(0);
+                load_stage(s0, ch + NWC, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                compute(acc[1]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (++since == 8) {
+                    since = 0;
+#pragma unroll
+                    for (int r = 0; r < 2; ++r) {
+                        tot[r] += acc[r];
+                        acc[r] = f32x16{0};
+                    }
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 2; ++r) tot[r] += acc[r];
+
+            // ---- the waves of each row group, added in wave order ----
+            // a wave's own tile first (nobody else touches it), then the sums in place
+#pragma unroll
+            for (int rt = 0; rt < 2; ++rt)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) stg[(rt * 16 + v) * 64 + lane] = tot[rt][v];
+            __syncthreads();
+            for (int e = tid; e < RG * 2048; e += 64 * NW) {
+                float *p0 = lds + (e >> 11) * (NWC * 2048) + (e & 2047);
+                float t = p0[0];
+#pragma unroll
+                for (int ww = 1; ww < NWC; ++ww) t += p0[ww * 2048];
+                p0[0] = t;
+            }
+            __syncthreads();                       // the other tiles change hands
+        }
+
+        // ---- H H^T from the partial tile sets, and the block's rows of W ----
+        if (mode != 1) {
+            for (int e = tid; e < 32 * 32; e += 64 * NW) {
+                const int c = e >> 5, d = e & 31;
+                // stacked independent runs: factor indices of different runs do not interact
+                const bool in = c < k && d < k && (!bm.on || bm.id[c] == bm.id[d]);
+                const float v = GH[in ? c * k + d : 0];
+                Gs[c * LDW + d] = in ? v : 0.f;
+            }
+        }
+        for (int e = tid; e < RB * 32; e += 64 * NW) {
+            const int i = e >> 5, c = e & 31;
+            const bool in = i0 + i < rows && c < k;
+            const float v = W[in ? (i0 + i) * k + c : 0];
+            (mode != 1 ? Ws : Wn)[i * LDW + c] = in ? v : 0.f;
+        }
+        __syncthreads();
+        if (mode != 1) {
+            for (int e = tid; e < RB * 32; e += 64 * NW) {
+                const int i = e >> 5, c = e & 31;
+                float wn = 0.f;
+                if (i0 + i < rows && c < k) {
+                    float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
+                    const float *wr = Ws + i * LDW;
+#pragma unroll
+                    for (int d = 0; d < 32; d += 4) {
+                        d0 += wr[d + 0] * Gs[(d + 0) * LDW + c];
+                        d1 += wr[d + 1] * Gs[(d + 1) * LDW + c];
+                        d2 += wr[d + 2] * Gs[(d + 2) * LDW + c];
+                        d3 += wr[d + 3] * Gs[(d + 3) * LDW + c];
+                    }
+                    const float den = ((d0 + d1) + (d2 + d3)) + eps;
+                    const int r = i & 31;
+                    const float q = lds[(i >> 6) * (NWC * 2048) +
+                                        ((((i >> 5) & 1) * 16 + ((r & 3) | ((r >> 3) << 2))) * 64) + 32 * ((r >> 2) & 1) + c];
+                    wn = wr[c] * q / den;
+                    if (mode == 0) W[(i0 + i) * k + c] = wn;
+                    dacc += (double)q * (double)wn;
+                }
+                Wn[i * LDW + c] = wn;
+            }
+            __syncthreads();
+        }
+        // ---- by-products of the new rows: piece planes, Gram share ----
+        if (tid < (RB / 8) * 32) {
+            const int gl = tid >> 5, c = tid & 31;
+            const int64_t grow = (i0 >> 3) + gl;
+            if (grow * 8 < rows && mode != 2) {
+                u32x4 o[3];
+#pragma unroll
+                for (int pr = 0; pr < 4; ++pr) {
+                    unsigned hh[2], mm[2], ll[2];
+#pragma unroll
+                    for (int e = 0; e < 2; ++e) split3(Wn[(8 * gl + 2 * pr + e) * LDW + c], hh[e], mm[e], ll[e]);
+                    o[0][pr] = pack2(hh[0], hh[1]);
+                    o[1][pr] = pack2(mm[0], mm[1]);
+                    o[2][pr] = pack2(ll[0], ll[1]);
+                }
+#pragma unroll
+                for (int pl = 0; pl < 3; ++pl) planesW[(grow * 3 + pl) * 32 + c] = o[pl];
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < RB / 16; ++q) {
+            const float va = Wn[(2 * (w + NW * q) + half) * LDW + jj];
+            gacc = mfma32(va, va, gacc);
+        }
+        __syncthreads();                           // LDS goes back to the staging tiles
+    }
+
+    if (dpart) {
+        for (int off = 32; off > 0; off >>= 1) dacc += __shfl_xor(dacc, off);
+        if (lane == 0) dsum[w] = dacc;
+        __syncthreads();
+        if (tid == 0) {
+            double t = 0.0;
+            for (int i = 0; i < NW; ++i) t += dsum[i];
+            dpart[blockIdx.x] = t;
+        }
+    }
+    // this workgroup's share of W^T W: the eight waves' tiles added in wave order
+#pragma unroll
+    for (int v = 0; v < 16; ++v) lds[w * 1024 + v * 64 + lane] = gacc[v];
+    __syncthreads();
+    for (int e = tid; e < 1024; e += 64 * NW) {
+        float t = lds[e];
+#pragma unroll
+        for (int ww = 1; ww < NW; ++ww) t += lds[ww * 1024 + e];
+        gout[(int64_t)blockIdx.x * 1024 + e] = t;
+    }
+}
+
 // G (k x k, ld k) = sum over nb sets of partial 32 x 32 tiles (accumulator layout).
 // Eight lanes share one entry: lane q adds sets q, q+8, ... in order, then the
 // eight sums are combined in a fixed tree, so the result does not depend on timing.
@@ -1814,6 +2099,44 @@ hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const
     case 2: aht_dispatch<2>(vec, grid, st, A, H, GH, W, rows, n, k, eps, dpart); break;
     default: return hipErrorInvalidValue;
     }
+    return hipGetLastError();
+}
+
+bool aht_rows_ok(const float *A, int64_t m, int64_t n, int k)
+{
+    // 32 rows of A are addressed with 32-bit byte offsets: 128 n < 2^31.  Short and wide matrices
+    // leave most of the chip without a row block: they keep the other plans, unless the whole
+    // problem is small enough to be latency bound anyway.
+    return k <= 32 && vec_ok(A, n) && n < ((int64_t)1 << 24) && (m >= 4096 || m * n <= ((int64_t)1 << 22));
+}
+
+static int aht_rows_groups(int64_t rows) { return (rows + 127) / 128 >= 192 ? 2 : 1; }
+
+int aht_rows_blocks(int64_t rows)
+{
+    const int64_t rb = 64 * aht_rows_groups(rows);
+    int64_t b = (rows + rb - 1) / rb;
+    if (b > kFinMaxBlocks) b = kFinMaxBlocks;
+    return (int)b;
+}
+
+hipError_t launch_aht_rows(const float *A, int64_t rows, int64_t n, int k, const void *planesH,
+                           const float *GH, float *W, void *planesW, float *gout, float eps, hipStream_t st,
+                           bool gram_only, const BlockMap *map, double *dpart, bool dry)
+{
+    if (k > 32 || !planesW || !gout) return hipErrorInvalidValue;
+    if (!gram_only && (!A || !planesH || !GH || !vec_ok(A, n) || n >= ((int64_t)1 << 24))) return hipErrorInvalidValue;
+    BlockMap bm;
+    if (map) bm = *map;
+    else bm.on = 0;
+    const dim3 grid((unsigned)aht_rows_blocks(rows)), block(512);
+    const u32x4 *ph = static_cast<const u32x4 *>(planesH);
+    u32x4 *pw = static_cast<u32x4 *>(planesW);
+    const int mode = gram_only ? 1 : (dry ? 2 : 0);
+    if (aht_rows_groups(rows) == 2)
+        hipLaunchKernelGGL((aht_rows_kernel<2>), grid, block, 0, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
+    else
+        hipLaunchKernelGGL((aht_rows_kernel<1>), grid, block, 0, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
     return hipGetLastError();
 }
 

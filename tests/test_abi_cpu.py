@@ -57,9 +57,9 @@ def test_workspace_bytes():
     assert wb(7, 10, 10, 0, 4, 0) == 0         # unknown kind
     assert wb(2, 10, 10, 0, 4, 0) == 0         # ooc needs batch_rows
     d = wb(4, 32768, 16384, 0, 32, 0)
-    # small plan: 4 row splits of a 32 x 16384 fp32 partial, the bf16 piece planes of W
-    # (3 pieces x 64 factor slots x 16 bytes per group of 8 rows) and the Gram scratch
-    base = 4 * 32 * 16384 * 4 + (32768 // 8) * 3 * 64 * 16
+    # small plan: 4 row splits of a 32 x 16384 fp32 partial, the bf16 piece planes of W and of
+    # H^T (3 pieces x 64 factor slots x 16 bytes per group of 8 rows) and the Gram scratch
+    base = 4 * 32 * 16384 * 4 + ((32768 + 16384) // 8) * 3 * 64 * 16
     assert base <= d <= base + (4 << 20)
     # fast plan: additionally A^T, W^T and H^T
     extra = (32768 * 16384 + 32 * 32768 + 16384 * 32) * 4

@@ -431,14 +431,14 @@ def test_ooc_equals_small_plan_dense_bitwise_when_one_batch():
     """With one batch the out-of-memory path launches the same kernels as the
     resident path without the transposed copy of A (forced here by a caller
     workspace too small for that copy)."""
-    A, W, H = case(640, 512, 32, 80)
-    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, 640, 512, 0, 32, 0), dtype=torch.uint8, device="cuda")
+    A, W, H = case(640, 512, 48, 80)     # above 32 factors the resident path has no plan of its own
+    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, 640, 512, 0, 48, 0), dtype=torch.uint8, device="cuda")
     nmf.nmf_mu_set_workspace(buf)
     try:
         Wg, Hg = run_dense(A, W, H, 4)
         Ah = torch.from_numpy(A).pin_memory()
         Wd, Hd = dev(W), dev(H)
-        nmf.nmf_mu_ooc(Ah, 640, 512, 32, Wd, Hd, 4, EPS, 640, 1 << 30)
+        nmf.nmf_mu_ooc(Ah, 640, 512, 48, Wd, Hd, 4, EPS, 640, 1 << 30)
         np.testing.assert_array_equal(host(Wd), Wg)
         np.testing.assert_array_equal(host(Hd), Hg)
     finally:
@@ -465,7 +465,7 @@ def test_profile_entry_reports_plan_and_times():
     A, W, H = case(512, 384, 8, 33)
     Wd, Hd = dev(W), dev(H)
     ms = nmf.nmf_mu_dense_profile(dev(A), 512, 384, 8, Wd, Hd, 3, EPS)
-    assert len(ms) == 9 and ms[6] == 1.0 and all(x >= 0 for x in ms[:6]) and ms[1] > 0 and ms[4] > 0
+    assert len(ms) == 9 and ms[6] == 2.0 and all(x >= 0 for x in ms[:6]) and ms[1] > 0 and ms[4] > 0
     assert ms[7] > 0 and ms[8] > 0
     # the timing launches leave the result alone: same bits as the plain entry point
     Wg, Hg = run_dense(A, W, H, 3)
