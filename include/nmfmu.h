@@ -8,9 +8,15 @@
  *     H <- H * (W^T A) / ((W^T W) H + eps)          H update, old H on the right
  *     W <- W * (A H^T) / (W (H H^T) + eps)          W update, uses the NEW H
  *
- * eps is added once, to the finished denominator.  Arithmetic is IEEE single
- * precision throughout (products on the matrix cores with fp32 operands and
- * fp32 accumulation).
+ * eps is added once, to the finished denominator.  Operands and results are
+ * IEEE single precision.  For k <= NMF_MU_MAX_K and 16-byte aligned A the two
+ * products over A are formed on the bf16 matrix cores from exact pieces: every
+ * float is cut into three bf16 values that add up to it bit for bit, all nine
+ * piece products of a term are accumulated in fp32 (each is exact there), and
+ * no matrix accumulator runs over more than 512 terms before it is added, in
+ * rounded fp32, to a running total; long sums stay within 3e-7 relative of the
+ * float64 result.  Unaligned A and the Gram matrices use the fp32 matrix
+ * instruction (fp32 operands, fp32 accumulation).
  *
  * Conventions shared by every entry point
  *   - All matrices are row-major and contiguous: A is m x n (leading dimension
@@ -29,9 +35,14 @@
  *     device; on return all of its work is ordered before anything enqueued
  *     on `stream` afterwards.
  *   - Scratch memory (partial sums, Gram matrices) comes from a per-process
- *     workspace that the library allocates on first use and grows on demand,
- *     or from a caller-provided block (nmf_mu_set_workspace).  Calls that run
- *     concurrently on one device share it and therefore race: serialise them.
+ *     workspace that the library allocates on first use and grows on demand
+ *     (growing it synchronises the device), or from a caller-provided block
+ *     (nmf_mu_set_workspace).  There is one workspace per process: the calls
+ *     of this header hold a lock while they enqueue, so they may be made from
+ *     several threads, but work that two of them leave in flight on different
+ *     streams at the same time shares the workspace and races.  Run one
+ *     problem at a time per process, or order the streams with events.  Only
+ *     nmf_mu_dense_noalloc has scratch of its own (shared by its own calls).
  *   - Every function returns a status code and never throws, exits or prints.
  *     Entries of A, W, H are not inspected: negative or non-finite input gives
  *     an undefined (but non-faulting) result.  iters == 0 is a successful
@@ -71,10 +82,14 @@ const char *nmf_last_error(void);
  *   A      device, m x n, read-only
  *   W, H   device, in/out
  *   iters  >= 0;  eps >= 0 and finite
- * Asynchronous on `stream`.  If the workspace can hold a second copy of A the
- * library transposes A once per call and streams A^T for the A H^T product
- * (both passes then read memory in row order); otherwise it runs a direct
- * A H^T kernel on A.  Both give the same iteration; low-order bits differ.
+ * Asynchronous on `stream`.  Three plans, chosen per call; they give the same
+ * iteration and differ in low-order bits.  Row plan (k <= 32, 16-byte aligned
+ * A, n % 4 == 0, n < 2^24, and m >= 4096 or m n <= 2^22): both products stream
+ * the row-major A, the W update is fused into the A H^T pass; workspace kind 4.
+ * Mirrored plan (other shapes, if the workspace can hold a second copy of A):
+ * A is transposed once per call and A^T is streamed for the A H^T product;
+ * workspace kind 0.  Small plan otherwise: a direct A H^T kernel on A (lanes
+ * down the rows: slower); workspace kind 4.
  * Ranks NMF_MU_MAX_K < k <= NMF_MU_MAX_K_SLICED run the same iteration with every
  * product written as F^T X (a reduction over the rows of two row-major
  * matrices) and computed 64 factor columns of F at a time by the k <= 64 pass
@@ -107,27 +122,6 @@ int nmf_mu_dense(const float *A, int64_t m, int64_t n, int32_t k,
 #define NMF_MU_NOALLOC_SCRATCH_BYTES (32u << 20)
 int nmf_mu_dense_noalloc(const float *A, int64_t m, int64_t n, int32_t k,
                          float *W, float *H, int32_t iters, float eps, void *stream);
-
-/*
- * nmf_mu_dense with timing: the same launches on `stream`, with a HIP event
- * recorded between them; synchronises `stream` before returning.  On return
- * kernel_ms[0..5] (HOST memory, 9 floats) hold the average milliseconds per
- * launch of the kernels of one iteration, in launch order:
- *   [0] W^T W   [1] W^T A pass   [2] H update   [3] H H^T
- *   [4] A H^T pass (on the mirrored copy A^T, or the direct kernel with the W
- *       update fused)   [5] W update (0 for the direct kernel)
- * and kernel_ms[6] names the plan that ran: 2 the row plan (k <= 32, aligned A:
- * both passes stream the row-major A, [0], [3] and [5] are 0 because the Gram
- * matrices and the W update are by-products of the other three kernels), 1 the
- * mirrored plan (see nmf_mu_workspace_bytes), 0 the small plan.  kernel_ms[7] and
- * [8]: milliseconds per launch of the W^T A pass and (plans 1 and 2, else 0) of
- * the A H^T pass, from 20 launches back to back between two events after the
- * run, i.e. without the event commands that surround every kernel in [0..5].
- * 1 <= iters <= 4096.
- */
-int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k,
-                         float *W, float *H, int32_t iters, float eps, void *stream,
-                         float *kernel_ms);
 
 /*
  * Objective of the factorisation, ||A - W H||_F (section 2.1; Algorithm 1
@@ -180,9 +174,13 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
  * workspace, a column-ordered copy of the matrix (8 bytes per stored entry plus
  * 8 (n + 1) bytes) and a transposed copy of H; both products then gather rows
  * of a factor per stored entry, without atomics, so results are reproducible
- * from run to run.  Needs nnz < 2^31 and m < 2^31.  The build sorts with
- * transient scratch memory (about 24 bytes per stored entry) and synchronises
- * `stream` once; the iterations are then enqueued asynchronously.
+ * from run to run.  Needs nnz < 2^31 and m < 2^31.  The build is a stable sort
+ * by column on `stream` whose scratch (about 24 bytes per stored entry) is part
+ * of the workspace; the whole call only enqueues work and returns.  The
+ * structure is not validated (that would need the device's answer): entry
+ * ranges and column indices are clamped to the arrays' bounds where they are
+ * used, so malformed row pointers or indices give a meaningless result but no
+ * out-of-range access.
  */
 int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                int64_t m, int64_t n, int64_t nnz, int32_t k,
@@ -195,12 +193,12 @@ int nmf_mu_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
  * ||A||^2 - 2 <A H^T, W> + <H H^T, W^T W>, the only form that does not touch the
  * m n entries of W H: <A H^T, W> is summed in double inside the W update from the
  * gathered row sums against the new W, H H^T is the matrix the update used,
- * W^T W of the new W costs one more read of W per iteration, ||A||^2 (sum of the
- * squared stored values; repeated (row, column) pairs would have to be added
- * first, so the value assumes there are none) once per call.  Absolute error
+ * W^T W of the new W costs one more read of W per iteration, ||A||^2 once per
+ * call (the squared stored values, plus the cross terms of repeated (row,
+ * column) pairs, which stand for their sum).  Absolute error
  * about 2e-7 ||A||^2 / f as for nmf_mu_dense_monitor.  objective_host: HOST
  * memory, iters doubles.  Blocking.  W, H as nmf_mu_csr (bit-identical result).
- * The workspace is nmf_mu_workspace_bytes(kind 1) plus 8 (iters + 8449) bytes,
+ * The workspace is nmf_mu_workspace_bytes(kind 1) plus 8 (iters + 73986) bytes,
  * rounded up to 256-byte pieces.
  */
 int nmf_mu_csr_monitor(const int64_t *rowptr, const int32_t *colidx, const float *vals,
@@ -324,10 +322,11 @@ int nmf_mu_dense_batched(int32_t n_runs, const float *const *A, int64_t m, int64
                          int32_t iters, float eps, void *stream);
 
 /*
- * Workspace the given problem needs, in bytes.  kind: 0 dense (fast plan: the
- * library keeps a transposed copy of A, so this is about m*n*4 bytes plus the
- * partial sums), 4 dense (small plan: partial sums only; used automatically
- * when the fast plan's workspace cannot be had), 1 csr, 2 ooc (excluding the
+ * Workspace the given problem needs, in bytes.  kind: 0 dense (mirrored plan:
+ * the library keeps a transposed copy of A, so this is about m*n*4 bytes plus
+ * the partial sums), 4 dense (row plan and small plan: partial sums and operand
+ * planes only), 1 csr (includes the scratch of the one-time sort, about 24 bytes
+ * per stored entry), 2 ooc (excluding the
  * staging slots), 3 batched (enough for any mix of ranks; k is only checked),
  * 5 dense with k > NMF_MU_MAX_K (rank-sliced), 6 the rank-sliced out-of-memory
  * pipeline (nmf_mu_ooc_hostw, and nmf_mu_ooc above NMF_MU_MAX_K; excluding the
@@ -345,56 +344,6 @@ int nmf_mu_set_workspace(void *dev_ptr, size_t bytes);
 
 /* Free library-owned workspace and staging memory (synchronises the device). */
 int nmf_mu_release(void);
-
-/* ---- single steps, exposed for testing and profiling (same conventions) ---- */
-
-/* The row-balanced work partition of the sparse kernels: part[0 .. nparts]
- * (device, int64) with part[w] = first row r such that
- * rowptr[r] + 8 r >= w * ceil((rowptr[m] + 8 m) / nparts) and part[nparts] = m;
- * wavefront w of a sparse update works on rows [part[w], part[w + 1]).  The
- * library uses nparts = 16384 and sends rows with more than 16384 stored
- * entries to a whole workgroup instead.  Asynchronous on `stream`. */
-int nmf_csr_partition(const int64_t *rowptr, int64_t m, int32_t nparts, int64_t *part, void *stream);
-
-/* The operand encoding of the W^T A pass for k <= 64.  The products of
- * Algorithms 2-5 (W^T A, and A H^T as the same product on the transposes) are
- * formed on the bf16 matrix cores from exact pieces: a float x is cut into
- * x = h + m + l, h = x with its significand truncated to 8 bits, m = x - h
- * truncated likewise, l = x - h - m (each piece is a bf16, the sum is x bit
- * for bit for |x| >= 2^-110); all nine piece products of a term are
- * accumulated in fp32.  This call writes the pieces of X (rows x k, row-major,
- * device, k <= 64) as the kernels read them, with KP = 32 factor slots per
- * row group for k <= 32 and KP = 64 above: for row group g = row / 8, piece
- * p (0: h, 1: m, 2: l) and factor c < KP, the eight bf16 of rows 8g .. 8g+7 at
- * planes[((g * 3 + p) * KP + c) * 8 ..]; rows >= `rows` and factors >= k are
- * zero.  `planes`: device, ceil(rows / 8) * 24 * KP uint16.  Asynchronous. */
-int nmf_split_planes(const float *X, int64_t rows, int32_t k, uint16_t *planes, void *stream);
-
-/* Column-ordered copy of a CSR matrix, the structure nmf_mu_csr derives for its
- * W^T A product: colptr int64[n + 1], rowidx int32[nnz], cvals float[nnz] (all
- * device, caller-allocated).  Entries of a column keep the order in which the
- * CSR arrays store them (stable).  Synchronises `stream`. */
-int nmf_csr_to_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals,
-                   int64_t m, int64_t n, int64_t nnz,
-                   int64_t *colptr, int32_t *rowidx, float *cvals, void *stream);
-
-/* G (k x k, ld k) = W^T W.  Algorithm 3, formation of WTW. */
-int nmf_gram_w(const float *W, int64_t m, int32_t k, float *G, void *stream);
-
-/* P (k x n, ld n) = W^T A for dense A.  Algorithm 3, formation of WTA. */
-int nmf_wta_dense(const float *A, int64_t m, int64_t n, int32_t k,
-                  const float *W, float *P, void *stream);
-
-/* H <- H * P / (G H + eps) in place and GH (k x k) = H H^T of the new H.
- * Algorithm 3, the H-update line and the formation of HHT.  GH may be NULL. */
-int nmf_h_update(float *H, const float *P, const float *G, int32_t k, int64_t n,
-                 float eps, float *GH, void *stream);
-
-/* W <- W * (A H^T) / (W GH + eps) in place, A dense.  Algorithm 3, formation
- * of AHT and WHHT and the W-update line, fused. */
-int nmf_aht_w_update_dense(const float *A, int64_t m, int64_t n, int32_t k,
-                           const float *H, const float *GH, float *W,
-                           float eps, void *stream);
 
 #ifdef __cplusplus
 }

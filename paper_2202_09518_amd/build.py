@@ -24,7 +24,8 @@ def is_stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "nmfmu_internal.h"), os.path.join(ROOT, "include", "nmfmu.h")]
+    deps = sources() + [os.path.join(CSRC, "nmfmu_internal.h"), os.path.join(ROOT, "include", "nmfmu.h"),
+                        os.path.join(ROOT, "include", "nmfmu_test.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

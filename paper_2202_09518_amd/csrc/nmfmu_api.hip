@@ -1,7 +1,8 @@
 // C ABI of libnmfmu: argument checking, workspace management and the host-side
 // schedules (resident loop, out-of-memory batch pipeline, CSR loop, ensemble).
-// Public contract: include/nmfmu.h.
+// Public contract: include/nmfmu.h; the hooks of the tests: include/nmfmu_test.h.
 #include "nmfmu.h"
+#include "nmfmu_test.h"
 #include "nmfmu_internal.h"
 
 #include <algorithm>
@@ -325,11 +326,14 @@ size_t csr_bytes(int64_t n, int64_t nnz, int k)
            align_up((size_t)nnz * sizeof(int32_t)) + align_up((size_t)nnz * sizeof(float)) +
            2 * align_up((size_t)(kCsrParts + 1) * sizeof(int64_t)) +          // row ranges, CSR and CSC
            2 * align_up((size_t)(nnz / kLongRow + 2) * sizeof(int32_t)) +     // long-row lists
-           kAlign;                                                            // their counts
+           kAlign +                                                           // their counts
+           // scratch of the one-time sort that builds the column-ordered copy
+           align_up((size_t)nnz * sizeof(int32_t)) + 2 * align_up((size_t)nnz * sizeof(uint64_t)) +
+           align_up(nnz ? csc_sort_temp_bytes(nnz, n) : 0);
 }
 
-// Column-ordered copy of a CSR matrix; the sort scratch is transient (allocated
-// and freed here, which synchronises with `st`).
+// Column-ordered copy of a CSR matrix into caller-provided arrays (test hook); the sort
+// scratch is transient (allocated and freed here, which synchronises with `st`).
 int build_csc(const int64_t *rowptr, const int32_t *colidx, const float *vals, int64_t m,
               int64_t n, int64_t nnz, int64_t *colptr, int32_t *rowidx, float *cvals, hipStream_t st)
 {
@@ -1051,7 +1055,7 @@ int nmf_mu_ooc_hostw(const float *A_host, float *W_host, int64_t m, int64_t n, i
 size_t csr_monitor_bytes(int iters)
 {
     return align_up((size_t)kCsrDparts * sizeof(double)) + align_up(4097 * sizeof(double)) +
-           align_up((size_t)iters * sizeof(double));
+           align_up((size_t)iters * sizeof(double)) + align_up((size_t)(65536 + 1) * sizeof(double));
 }
 
 // Stopping rule of a sparse run (Algorithm 1): results in host memory.
@@ -1092,22 +1096,36 @@ static int csr_run(const int64_t *rowptr, const int32_t *colidx, const float *va
     int32_t *long_r = cv.take<int32_t>((size_t)(nnz / kLongRow + 2));
     int32_t *long_c = cv.take<int32_t>((size_t)(nnz / kLongRow + 2));
     unsigned *long_n = cv.take<unsigned>(64);      // [0] rows of A, [1] columns of A
-    double *dpart = nullptr, *normA2 = nullptr, *obj = nullptr;
+    const size_t sort_temp_bytes = nnz ? csc_sort_temp_bytes(nnz, n) : 0;
+    int32_t *sorted_cols = cv.take<int32_t>((size_t)nnz);
+    uint64_t *payload = cv.take<uint64_t>((size_t)nnz);
+    uint64_t *sorted_payload = cv.take<uint64_t>((size_t)nnz);
+    char *sort_temp = cv.take<char>(sort_temp_bytes);
+    double *dpart = nullptr, *normA2 = nullptr, *obj = nullptr, *dup = nullptr;
     if (watch) {
         dpart = cv.take<double>(kCsrDparts);
         normA2 = cv.take<double>(4097);
         obj = cv.take<double>(tolp ? 1 : (size_t)iters);
-        if (nnz > 0) NMF_HIP(launch_sumsq(vals, nnz, normA2 + 1, normA2, st));
-        else NMF_HIP(hipMemsetAsync(normA2, 0, sizeof(double), st));
+        dup = cv.take<double>(65536 + 1);      // one share per block of the copy's last kernel, then the sum of squares
     }
+    const int ndup = csc_finish_blocks(nnz);
 
-    if (int rc = build_csc(rowptr, colidx, vals, m, n, nnz, colptr, rowidx, cvals, st)) return rc;
+    // Column-ordered copy of A, once per call, enqueued like everything else.
+    NMF_HIP(launch_csc_build(rowptr, colidx, vals, m, n, nnz, sorted_cols, payload, sorted_payload, sort_temp,
+                             sort_temp_bytes, colptr, rowidx, cvals, st, dup));
+    if (watch) {
+        // ||A||_F^2 of the matrix the arrays stand for: the squared stored values plus what repeated
+        // (row, column) pairs add (found while the column-ordered copy is written)
+        if (nnz > 0) NMF_HIP(launch_sumsq(vals, nnz, normA2 + 1, dup + ndup, st));
+        else NMF_HIP(launch_fill_f32(reinterpret_cast<float *>(dup + ndup), 2, 0.f, st));
+        NMF_HIP(launch_sum_f64(dup, ndup + 1, normA2, st));
+    }
 
     // Work partitions of both orientations, once per call.
     NMF_HIP(launch_csr_partition(rowptr, m, kCsrParts, part_r, st));
     NMF_HIP(launch_csr_partition(colptr, n, kCsrParts, part_c, st));
-    NMF_HIP(launch_csr_long_rows(rowptr, m, long_r, long_n, st));
-    NMF_HIP(launch_csr_long_rows(colptr, n, long_c, long_n + 1, st));
+    NMF_HIP(launch_csr_long_rows(rowptr, m, long_r, long_n, (unsigned)(nnz / kLongRow + 1), st));
+    NMF_HIP(launch_csr_long_rows(colptr, n, long_c, long_n + 1, (unsigned)(nnz / kLongRow + 1), st));
 
     NMF_HIP(launch_transpose(H, k, n, Ht, st));
     // One iteration; with `out`, ||A - W H||_F of its result goes there, from what the W update
@@ -1115,9 +1133,9 @@ static int csr_run(const int64_t *rowptr, const int32_t *colidx, const float *va
     // computes the same matrix again for its H update).
     auto iteration = [&](double *out) -> int {
         NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
-        NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, W, c.gw, Ht, eps, st));   // H update on H^T
+        NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, W, c.gw, Ht, eps, nnz, m, st));   // H update on H^T
         NMF_HIP(launch_gram_w_wide(Ht, n, k, c.gh, c.ghp, st));
-        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st, false,
+        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, nnz, n, st, false,
                                out ? dpart : nullptr));                                                       // W update
         if (out) {
             NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
@@ -1130,7 +1148,7 @@ static int csr_run(const int64_t *rowptr, const int32_t *colidx, const float *va
         double res = 0.0;
         NMF_HIP(launch_gram_w_wide(W, m, k, c.gw, c.gwp, st));
         NMF_HIP(launch_gram_w_wide(Ht, n, k, c.gh, c.ghp, st));
-        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, st, false, dpart, true));
+        NMF_HIP(launch_aht_csr(rowptr, colidx, vals, part_r, long_r, long_n, k, Ht, c.gh, W, eps, nnz, n, st, false, dpart, true));
         NMF_HIP(launch_objective(dpart, kCsrDparts, c.gw, c.gh, k, normA2, obj, st));
         NMF_HIP(hipMemcpyAsync(&res, obj, sizeof(double), hipMemcpyDeviceToHost, st));
         NMF_HIP(hipStreamSynchronize(st));
@@ -1308,16 +1326,16 @@ int nmf_mu_csr_ooc(const int64_t *rowptr_host, const int32_t *colidx_host, const
             float *Wb = W + bt.r0 * k;
             if (s > 0) {
                 NMF_HIP(launch_csr_partition(rowptr_loc, rows, kCsrParts, part_r, st));
-                NMF_HIP(launch_csr_long_rows(rowptr_loc, rows, long_r, long_n, st));
-                NMF_HIP(launch_aht_csr(rowptr_loc, ci, va, part_r, long_r, long_n, k, Ht, c.gh, Wb, eps, st));
+                NMF_HIP(launch_csr_long_rows(rowptr_loc, rows, long_r, long_n, (unsigned)(max_nnz / kLongRow + 1), st));
+                NMF_HIP(launch_aht_csr(rowptr_loc, ci, va, part_r, long_r, long_n, k, Ht, c.gh, Wb, eps, cnt, n, st));
             }
             if (s < iters) {
                 NMF_HIP(launch_csc_build(rowptr_loc, ci, va, rows, n, cnt, sorted_cols, payload, sorted_payload,
                                          sort_temp, temp_bytes, colptr, rowidx, cvals, st));
                 NMF_HIP(launch_csr_partition(colptr, n, kCsrParts, part_c, st));
-                NMF_HIP(launch_csr_long_rows(colptr, n, long_c, long_n + 1, st));
+                NMF_HIP(launch_csr_long_rows(colptr, n, long_c, long_n + 1, (unsigned)(max_nnz / kLongRow + 1), st));
                 NMF_HIP(launch_aht_csr(colptr, rowidx, cvals, part_c, long_c, long_n + 1, k, Wb, nullptr, Num, eps,
-                                       st, true));
+                                       cnt, rows, st, true));
             }
             NMF_HIP(hipEventRecord(g.sl_freed[slot], st));
         }

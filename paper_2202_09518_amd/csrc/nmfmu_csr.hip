@@ -88,12 +88,17 @@ __global__ __launch_bounds__(256) void csr_partition_kernel(const int64_t *__res
 }
 
 // list[0 .. *count) = rows with more than kLongRow entries (any order).
+// `cap` slots: row pointers that add up to nnz cannot name more such rows than nnz / kLongRow;
+// malformed ones can, and what does not fit is dropped (the count keeps running).
 __global__ __launch_bounds__(256) void csr_long_rows_kernel(const int64_t *__restrict__ rowptr,
                                                             int64_t m, int32_t *__restrict__ list,
-                                                            unsigned *count)
+                                                            unsigned *count, unsigned cap)
 {
     for (int64_t r = (int64_t)blockIdx.x * 256 + threadIdx.x; r < m; r += (int64_t)gridDim.x * 256)
-        if (rowptr[r + 1] - rowptr[r] > kLongRow) list[atomicAdd(count, 1u)] = (int32_t)r;
+        if (rowptr[r + 1] - rowptr[r] > kLongRow) {
+            const unsigned slot = atomicAdd(count, 1u);
+            if (slot < cap) list[slot] = (int32_t)r;
+        }
 }
 
 __global__ void zero_u32_kernel(unsigned *p) { if (threadIdx.x == 0 && blockIdx.x == 0) *p = 0u; }
@@ -101,11 +106,12 @@ __global__ void zero_u32_kernel(unsigned *p) { if (threadIdx.x == 0 && blockIdx.
 // One gather step of a lane group: entries [e, e + LPR) of a row (fewer at its
 // end), UNR at a time so that several table rows are in flight; lanes past the
 // end hold (column 0, value 0): they gather row 0 of the table and add nothing.
+// T has `trows` rows of k floats.
 template <int LPR>
 __device__ __forceinline__ float gather_chunk(const int32_t *__restrict__ colidx,
                                               const float *__restrict__ vals,
-                                              const float *__restrict__ T, int k, int c, int64_t e,
-                                              int64_t e1, float acc)
+                                              const float *__restrict__ T, int trows, int k, int c,
+                                              int64_t e, int64_t e1, float acc)
 {
     const int64_t left = e1 - e;
     const int cnt = left < LPR ? (left > 0 ? (int)left : 0) : LPR;
@@ -121,7 +127,8 @@ __device__ __forceinline__ float gather_chunk(const int32_t *__restrict__ colidx
         float a[UNR], h[UNR];
 #pragma unroll
         for (int u = 0; u < UNR; ++u) {
-            const int col = group_bcast<LPR>(colv, t0 + u);
+            // an index outside the table (malformed input) is pulled to its edge: no stray access
+            const int col = min(max(group_bcast<LPR>(colv, t0 + u), 0), trows - 1);
             a[u] = group_bcast<LPR>(valv, t0 + u);
             h[u] = T[(int64_t)col * k + cc];
         }
@@ -129,6 +136,13 @@ __device__ __forceinline__ float gather_chunk(const int32_t *__restrict__ colidx
         for (int u = 0; u < UNR; ++u) acc += a[u] * h[u];
     }
     return acc;
+}
+
+// The test that sends a row to the long-row kernel, on the row pointers as given (the list of
+// long rows is built with the same test).
+__device__ __forceinline__ bool rowptr_long(const int64_t *__restrict__ rowptr, int64_t row, bool valid)
+{
+    return valid && rowptr[row + 1] - rowptr[row] > kLongRow;
 }
 
 // ---------------------------------------------------------------------------
@@ -153,7 +167,7 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
                                                       const float *__restrict__ Ht,
                                                       const float *__restrict__ GH, float *W,
                                                       float eps, int accumulate,
-                                                      double *__restrict__ dpart)
+                                                      double *__restrict__ dpart, int64_t nnz, int trows)
 {
     constexpr int LDG = 65, RPW = 64 / LPR;
     __shared__ float Gs[64 * LDG];
@@ -167,15 +181,16 @@ __global__ __launch_bounds__(256) void aht_csr_kernel(const int64_t *__restrict_
     for (int64_t base = r_lo; base < r_hi; base += RPW) {
         const int64_t row = base + lane / LPR;
         bool valid = row < r_hi;
-        int64_t e = valid ? rowptr[row] : 0;
-        int64_t e1 = valid ? rowptr[row + 1] : 0;
-        if (e1 - e > kLongRow) {       // left to the long-row kernel
+        // row pointers outside [0, nnz] (malformed input) are pulled into the arrays
+        int64_t e = valid ? min(max(rowptr[row], (int64_t)0), nnz) : 0;
+        int64_t e1 = valid ? min(max(rowptr[row + 1], (int64_t)0), nnz) : 0;
+        if (rowptr_long(rowptr, row, valid)) {       // left to the long-row kernel
             valid = false;
             e1 = e;
         }
         float acc = 0.f;
         while (__any(e < e1)) {
-            acc = gather_chunk<LPR>(colidx, vals, Ht, k, c, e, e1, acc);
+            acc = gather_chunk<LPR>(colidx, vals, Ht, trows, k, c, e, e1, acc);
             e += LPR;
         }
         const float w = (valid && c < k) ? W[row * k + c] : 0.f;
@@ -214,12 +229,13 @@ __global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__rest
                                                            const float *__restrict__ Ht,
                                                            const float *__restrict__ GH, float *W,
                                                            float eps, int accumulate,
-                                                           double *__restrict__ dpart)
+                                                           double *__restrict__ dpart, int64_t nnz, int trows,
+                                                           unsigned list_cap)
 {
     constexpr int LDG = 65, NG = 256 / LPR;
     __shared__ float Gs[64 * LDG];
     __shared__ float part_acc[NG][LPR];
-    const unsigned n_long = *count;
+    const unsigned n_long = *count < list_cap ? *count : list_cap;
     if (n_long == 0) {
         if (dpart && threadIdx.x == 0) dpart[blockIdx.x] = 0.0;
         return;
@@ -229,10 +245,10 @@ __global__ __launch_bounds__(256) void aht_csr_long_kernel(const int64_t *__rest
     const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
     for (unsigned li = blockIdx.x; li < n_long; li += gridDim.x) {
         const int64_t row = list[li];
-        const int64_t e0 = rowptr[row], e1 = rowptr[row + 1];
+        const int64_t e0 = min(max(rowptr[row], (int64_t)0), nnz), e1 = min(max(rowptr[row + 1], (int64_t)0), nnz);
         float acc = 0.f;
         for (int64_t e = e0 + (int64_t)grp * LPR; __any(e < e1); e += (int64_t)NG * LPR)
-            acc = gather_chunk<LPR>(colidx, vals, Ht, k, c, e, e1, acc);
+            acc = gather_chunk<LPR>(colidx, vals, Ht, trows, k, c, e, e1, acc);
         part_acc[grp][c] = acc;
         __syncthreads();
         if (grp == 0) {        // LPR is a multiple of 64 only for LPR = 64; smaller groups share a wave
@@ -308,14 +324,14 @@ __global__ __launch_bounds__(256) void fill_f32_kernel(float *p, int64_t count, 
 // payload[e] = (row of entry e) << 32 | bits of vals[e]; a group of 32 lanes per row.
 __global__ __launch_bounds__(256) void csc_payload_kernel(const int64_t *__restrict__ rowptr,
                                                           const float *__restrict__ vals, int64_t m,
-                                                          uint64_t *__restrict__ payload)
+                                                          int64_t nnz, uint64_t *__restrict__ payload)
 {
     const int c = threadIdx.x & 31;
     const int64_t group = ((int64_t)blockIdx.x * 256 + threadIdx.x) >> 5;
     const int64_t ngroups = (int64_t)gridDim.x * 8;
     for (int64_t row = group; row < m; row += ngroups) {
-        const int64_t e1 = rowptr[row + 1];
-        for (int64_t e = rowptr[row] + c; e < e1; e += 32)
+        const int64_t e1 = min(max(rowptr[row + 1], (int64_t)0), nnz);
+        for (int64_t e = min(max(rowptr[row], (int64_t)0), nnz) + c; e < e1; e += 32)
             payload[e] = ((uint64_t)row << 32) | (uint64_t)__float_as_uint(vals[e]);
     }
 }
@@ -325,22 +341,43 @@ __global__ __launch_bounds__(256) void csc_payload_kernel(const int64_t *__restr
 // row indices and values and the column pointers (every column j with
 // sorted_cols[e'-1] < j <= sorted_cols[e'] starts at e'; columns after the last
 // stored one start at nnz).
+// dup_part (optional, one double per block): repeated (row, column) pairs stand for their sum, so
+// the squared norm of the matrix is the sum of the squared stored values plus, for every run of
+// entries with the same row and column (adjacent here, because the sort is stable and a column's
+// entries keep their row-major order), twice the products of its pairs; each entry adds
+// 2 x its value x the sum of the run's entries before it.
 __global__ __launch_bounds__(256) void csc_finish_kernel(const int32_t *__restrict__ sorted_cols,
                                                          const uint64_t *__restrict__ sorted_payload,
                                                          int64_t n, int64_t nnz,
                                                          int64_t *__restrict__ colptr,
                                                          int32_t *__restrict__ rowidx,
-                                                         float *__restrict__ cvals)
+                                                         float *__restrict__ cvals,
+                                                         double *__restrict__ dup_part)
 {
+    double corr = 0.0;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < nnz; e += (int64_t)gridDim.x * 256) {
         const uint64_t pl = sorted_payload[e];
         rowidx[e] = (int32_t)(pl >> 32);
         cvals[e] = __uint_as_float((unsigned)pl);
-        const int64_t cur = sorted_cols[e];
-        const int64_t prev = (e > 0) ? sorted_cols[e - 1] : -1;
+        if (dup_part) {
+            double before = 0.0;
+            for (int64_t p = e - 1; p >= 0 && sorted_cols[p] == sorted_cols[e] && (sorted_payload[p] >> 32) == (pl >> 32); --p)
+                before += (double)__uint_as_float((unsigned)sorted_payload[p]);
+            corr += 2.0 * (double)__uint_as_float((unsigned)pl) * before;
+        }
+        // column indices outside [0, n) (malformed input) are pulled to the edge
+        const int64_t cur = min(max((int64_t)sorted_cols[e], (int64_t)0), n - 1);
+        const int64_t prev = (e > 0) ? min(max((int64_t)sorted_cols[e - 1], (int64_t)0), n - 1) : -1;
         for (int64_t j = prev + 1; j <= cur; ++j) colptr[j] = e;
         if (e == nnz - 1)
             for (int64_t j = cur + 1; j <= n; ++j) colptr[j] = nnz;
+    }
+    if (dup_part) {     // uniform over the grid; lanes by butterfly, then the 4 waves in order
+        __shared__ double wsum[4];
+        for (int off = 32; off > 0; off >>= 1) corr += __shfl_xor(corr, off);
+        if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = corr;
+        __syncthreads();
+        if (threadIdx.x == 0) dup_part[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
     }
 }
 
@@ -394,29 +431,31 @@ hipError_t launch_csr_partition(const int64_t *rowptr, int64_t m, int nparts, in
 }
 
 hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list, unsigned *count,
-                                hipStream_t st)
+                                unsigned cap, hipStream_t st)
 {
     hipLaunchKernelGGL(zero_u32_kernel, dim3(1), dim3(64), 0, st, count);
     int64_t b = (m + 255) / 256;
     if (b > 4096) b = 4096;
-    hipLaunchKernelGGL(csr_long_rows_kernel, dim3((unsigned)b), dim3(256), 0, st, rowptr, m, list, count);
+    hipLaunchKernelGGL(csr_long_rows_kernel, dim3((unsigned)b), dim3(256), 0, st, rowptr, m, list, count, cap);
     return hipGetLastError();
 }
 
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
-                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
-                          bool accumulate, double *dpart, bool dry)
+                          int k, const float *Ht, const float *GH, float *W, float eps, int64_t nnz, int64_t trows,
+                          hipStream_t st, bool accumulate, double *dpart, bool dry)
 {
+    if (trows < 1 || trows > 0x7fffffff || nnz < 0) return hipErrorInvalidValue;
     if ((dpart && accumulate) || (dry && (!dpart || accumulate))) return hipErrorInvalidValue;
     const int lpr = lanes_per_row(k);
     const dim3 grid(kCsrParts / 4), block(256);
     const int acc = dry ? 2 : (accumulate ? 1 : 0);
     double *dlong = dpart ? dpart + kCsrParts / 4 : nullptr;
     NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_kernel<L>), grid, block, 0, st, rowptr, colidx,
-                                             vals, part, k, Ht, GH, W, eps, acc, dpart));
+                                             vals, part, k, Ht, GH, W, eps, acc, dpart, nnz, (int)trows));
     NMFMU_LPR_SWITCH(lpr, hipLaunchKernelGGL((aht_csr_long_kernel<L>), dim3(kCsrLongBlocks), block, 0, st, rowptr,
-                                             colidx, vals, long_list, long_count, k, Ht, GH, W, eps, acc, dlong));
+                                             colidx, vals, long_list, long_count, k, Ht, GH, W, eps, acc, dlong, nnz,
+                                             (int)trows, (unsigned)(nnz / kLongRow + 1)));
     return hipGetLastError();
 }
 
@@ -487,20 +526,23 @@ hipError_t launch_csc_build(const int64_t *rowptr, const int32_t *colidx, const 
                             int64_t m, int64_t n, int64_t nnz, int32_t *sorted_cols,
                             uint64_t *payload, uint64_t *sorted_payload, void *sort_temp,
                             size_t sort_temp_bytes, int64_t *colptr, int32_t *rowidx, float *cvals,
-                            hipStream_t st)
+                            hipStream_t st, double *dup_part)
 {
     if (nnz == 0) {
         hipLaunchKernelGGL(fill_i64_kernel, dim3(blocks_for(n + 1)), dim3(256), 0, st, colptr, n + 1, (int64_t)0);
+        if (dup_part) hipLaunchKernelGGL(fill_i64_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<int64_t *>(dup_part), (int64_t)1, (int64_t)0);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(csc_payload_kernel, dim3(blocks_for(m * 32)), dim3(256), 0, st, rowptr, vals, m, payload);
+    hipLaunchKernelGGL(csc_payload_kernel, dim3(blocks_for(m * 32)), dim3(256), 0, st, rowptr, vals, m, nnz, payload);
     hipError_t e = hipcub::DeviceRadixSort::SortPairs(sort_temp, sort_temp_bytes, colidx, sorted_cols,
                                                       (const uint64_t *)payload, sorted_payload,
                                                       (int)nnz, 0, bits_for(n), st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(csc_finish_kernel, dim3(blocks_for(nnz)), dim3(256), 0, st, sorted_cols,
-                       sorted_payload, n, nnz, colptr, rowidx, cvals);
+                       sorted_payload, n, nnz, colptr, rowidx, cvals, dup_part);
     return hipGetLastError();
 }
+
+int csc_finish_blocks(int64_t nnz) { return (int)blocks_for(nnz); }
 
 }  // namespace nmfmu

@@ -1,21 +1,25 @@
 // Dense kernels of the multiplicative-update iteration for gfx950 (MI355X).
 //
-// One iteration (paper, Algorithm 3 on a single unit) is five launches:
-//   gram_w   : WTW  = W^T W                       (k x k)
-//   wta_pass : WTA  = W^T A, as row-split partials (reads all of A)
-//   h_update : H   <- H * WTA / (WTW H + eps)
-//   gram_h   : HHT  = H H^T of the new H          (k x k)
-//   aht_pass : W   <- W * (A H^T) / (W HHT + eps) (reads all of A; A H^T and
-//              W HHT are never stored)
-//
-// Both passes over A are fp32 contractions with a small rank k, done on the
-// matrix cores with v_mfma_f32_32x32x2_f32: one instruction multiplies a
-// 32 x 2 by a 2 x 32 fp32 tile into a 32 x 32 fp32 accumulator and consumes
-// 64 elements of A, which at full issue rate is about what HBM delivers, so
-// the passes stay bandwidth bound.  A is read straight from global memory
-// into the operand registers (every element of A feeds exactly one
-// instruction, so staging it in LDS would buy nothing); LDS is used for the
-// cross-wave reductions and the fused update epilogue.
+// One iteration (paper, Algorithm 3 on a single unit) is
+//   WTW = W^T W,  WTA = W^T A,  H <- H * WTA / (WTW H + eps),
+//   HHT = H H^T (new H),  AHT = A H^T (new H),  W <- W * AHT / (W HHT + eps),
+// and the two products over A are all of its memory traffic.  Here they are
+// streaming passes over A on the matrix cores, with everything else folded into
+// them or into one small finisher kernel:
+//   wta_pass_split_buf_kernel / wta_pass_split64_wide_kernel : W^T A as row-split
+//       partials; lanes run along the columns of A, the reduction over rows is the
+//       reduction of the matrix instruction
+//   factor_update_kernel : sums the partials, updates H (or W^T in the mirrored
+//       plan), writes the operand planes and the Gram tiles of the new factor
+//   aht_rows_kernel : A H^T on the row-major A (coalesced loads turned through
+//       LDS) with the W update, the planes and the Gram tiles of the new W fused
+//   aht_pass_kernel : the older direct A H^T kernel (lanes down the rows), for
+//       shapes and ranks the others do not serve, and for the streamed batches
+//   gram_kernel, gram_sum_kernel, residual_*_kernel, objective_kernel : the small rest.
+// For k <= 64 and aligned A the products are exact: fp32 operands cut into three
+// bf16 pieces each, nine piece products per term on v_mfma_f32_32x32x16_bf16 with
+// fp32 accumulation (see split3 below).  wta_pass_kernel and aht_pass_kernel use
+// v_mfma_f32_32x32x2_f32 on the floats themselves.
 //
 // Lane layout of v_mfma_f32_32x32x2_f32 (64 lanes, D = A_op B_op + C):
 //   A_op (32 x 2):  lane l holds A_op[l % 32][l / 32]

@@ -134,13 +134,15 @@ constexpr int kCsrDparts = kCsrParts / 4 + kCsrLongBlocks;
 // rowptr[r] + kRowCost * r >= w * ceil((rowptr[m] + kRowCost * m) / nparts), part[nparts] = m.
 hipError_t launch_csr_partition(const int64_t *rowptr, int64_t m, int nparts, int64_t *part,
                                 hipStream_t st);
-// list[0 .. *count): the rows with more than kLongRow entries (list needs nnz / kLongRow + 1 slots).
+// list[0 .. min(*count, cap)): the rows with more than kLongRow entries (cap = nnz / kLongRow + 1 slots).
 hipError_t launch_csr_long_rows(const int64_t *rowptr, int64_t m, int32_t *list, unsigned *count,
-                                hipStream_t st);
+                                unsigned cap, hipStream_t st);
 hipError_t launch_aht_csr(const int64_t *rowptr, const int32_t *colidx, const float *vals,
                           const int64_t *part, const int32_t *long_list, const unsigned *long_count,
-                          int k, const float *Ht, const float *GH, float *W, float eps, hipStream_t st,
-                          bool accumulate = false, double *dpart = nullptr, bool dry = false);
+                          int k, const float *Ht, const float *GH, float *W, float eps, int64_t nnz, int64_t trows,
+                          hipStream_t st, bool accumulate = false, double *dpart = nullptr, bool dry = false);
+// nnz, trows: lengths of the entry arrays and of the table Ht (rows); row pointers and column
+// indices beyond them are pulled to the edge, so that malformed input cannot cause a stray access.
 // accumulate: X[i][:] += (gathered sum) instead of the update (GH unused).
 // dpart (updating launch only; kCsrDparts doubles): per workgroup of the two kernels, the sum of
 // gathered sum x new value over its rows, i.e. <A H^T, W_new> in pieces (objective monitor).
@@ -160,7 +162,10 @@ hipError_t launch_csc_build(const int64_t *rowptr, const int32_t *colidx, const 
                             int64_t m, int64_t n, int64_t nnz, int32_t *sorted_cols,
                             uint64_t *payload, uint64_t *sorted_payload, void *sort_temp,
                             size_t sort_temp_bytes, int64_t *colptr, int32_t *rowidx, float *cvals,
-                            hipStream_t st);
+                            hipStream_t st, double *dup_part = nullptr);
+// dup_part (csc_finish_blocks(nnz) doubles, at least one): their sum is what repeated (row, column)
+// pairs add to the squared Frobenius norm of the matrix beyond the sum of the squared stored values.
+int csc_finish_blocks(int64_t nnz);
 // out (cols x rows) = in^T.
 hipError_t launch_transpose(const float *in, int64_t rows, int64_t cols, float *out, hipStream_t st);
 

@@ -22,6 +22,27 @@ def declared_symbols():
     return sorted(names)
 
 
+def symbols_of(header):
+    text = open(os.path.join(ROOT, "include", header)).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(nmf_\w+)\s*\(", text)))
+
+
+def test_public_header_holds_the_boundary_and_nothing_else():
+    """nmfmu.h: status reporting, the four method calls and the workspace calls of the boundary,
+    the entry points of the next steps (objective and stopping rule, host-resident W, streamed
+    CSR) and the allocation-free variant; the single steps that tests and profiling use live in
+    nmfmu_test.h."""
+    boundary = ["nmf_status_string", "nmf_last_error", "nmf_mu_dense", "nmf_mu_csr", "nmf_mu_ooc",
+                "nmf_mu_dense_batched", "nmf_mu_workspace_bytes", "nmf_mu_set_workspace", "nmf_mu_release"]
+    next_steps = ["nmf_residual_dense", "nmf_mu_dense_tol", "nmf_mu_dense_monitor", "nmf_mu_csr_monitor",
+                  "nmf_mu_csr_tol", "nmf_mu_ooc_monitor", "nmf_mu_ooc_hostw", "nmf_mu_csr_ooc"]
+    assert symbols_of("nmfmu.h") == sorted(boundary + next_steps + ["nmf_mu_dense_noalloc"])
+    assert symbols_of("nmfmu_test.h") == sorted(
+        ["nmf_mu_dense_profile", "nmf_gram_w", "nmf_wta_dense", "nmf_h_update", "nmf_aht_w_update_dense",
+         "nmf_split_planes", "nmf_csr_partition", "nmf_csr_to_csc"])
+
+
 def test_library_exports_every_declared_symbol():
     L = nmf.lib()
     decl = declared_symbols()

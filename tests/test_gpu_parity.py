@@ -896,7 +896,7 @@ def csr_monitor_case(rowptr, colidx, vals, m, n, W, H, iters):
     Wd, Hd = dev(W), dev(H)
     got = np.array(nmf.nmf_mu_csr_monitor(dev(rowptr, torch.int64), dev(colidx, torch.int32), dev(vals), m, n,
                                           int(vals.size), k, Wd, Hd, iters, EPS))
-    normA2 = float(np.sum(vals.astype(np.float64) ** 2))
+    normA2 = float(np.sum(Ad.astype(np.float64) ** 2))
     bound = np.maximum(1e-5 * want, 3e-7 * normA2 / np.maximum(want, 1e-300))
     assert (np.abs(got - want) <= bound).all(), (got, want)
     Wg, Hg = run_csr(rowptr, colidx, vals, m, n, W, H, iters)
@@ -929,6 +929,53 @@ def test_csr_monitor_with_long_rows_and_empty_rows():
     vals = (1.0 - r.random(colidx.size, dtype=np.float32)).astype(np.float32)
     W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=178))
     csr_monitor_case(rowptr, colidx, vals, m, n, W, H, 3)
+
+
+def csr_with_repeated_entries(m, n, density, seed):
+    """A CSR matrix in which about a third of the stored positions appear two or three times
+    (the parts add up to the entry), the entries of a row in shuffled order."""
+    r = np.random.default_rng(seed)
+    Ad = (r.random((m, n)) * (r.random((m, n)) < density)).astype(np.float32)
+    rows = []
+    for i in range(m):
+        ent = []
+        for j in np.nonzero(Ad[i])[0]:
+            v = np.float32(Ad[i, j])
+            parts = int(r.integers(1, 4)) if r.random() < 0.35 else 1
+            cut = [np.float32(v * f) for f in r.dirichlet(np.ones(parts))] if parts > 1 else [v]
+            ent += [(int(j), float(c)) for c in cut]
+        order = r.permutation(len(ent))
+        rows.append([ent[t] for t in order])
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum([len(x) for x in rows])
+    colidx = np.array([j for row in rows for j, _ in row], dtype=np.int32)
+    vals = np.array([v for row in rows for _, v in row], dtype=np.float32)
+    return rowptr, colidx, vals
+
+
+def test_csr_monitor_and_tol_with_repeated_entries():
+    """Repeated (row, column) pairs stand for their sum: ||A||^2 in the objective's expansion is
+    that of the summed matrix, not the sum of the squared stored values (which is smaller here by
+    a tenth), in the reported objectives and in the stopping decision."""
+    import scipy.sparse as sp
+    m, n, k = 400, 300, 8
+    rowptr, colidx, vals = csr_with_repeated_entries(m, n, 0.08, 77)
+    Ad = np.asarray(sp.csr_matrix((vals, colidx, rowptr), shape=(m, n)).todense(), dtype=np.float32)
+    assert np.sum(vals.astype(np.float64) ** 2) < 0.95 * np.sum(Ad.astype(np.float64) ** 2)
+    W, H = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=78))
+    csr_monitor_case(rowptr, colidx, vals, m, n, W, H, 5)
+    eps = float(np.float32(EPS))
+    traj, Wr, Hr = [orc.residual_dense(Ad, W, H)], W, H
+    for _ in range(12):
+        Wr, Hr = orc.mu_csr(rowptr, colidx, vals, m, n, Wr, Hr, 1, eps)
+        traj.append(orc.residual_dense(Ad, Wr, Hr))
+    assert traj[7] < traj[6]
+    tol = 0.5 * (traj[6] + traj[7])
+    Wd, Hd = dev(W), dev(H)
+    done, res = nmf.nmf_mu_csr_tol(dev(rowptr, torch.int64), dev(colidx, torch.int32), dev(vals), m, n,
+                                   int(vals.size), k, Wd, Hd, 100, EPS, tol, 1)
+    assert done == 7
+    assert abs(res - traj[7]) <= 1e-4 * traj[7]
 
 
 @pytest.mark.parametrize("m,n,k,density,every", [(500, 700, 32, 0.05, 2), (300, 30000, 16, 0.002, 1)])
