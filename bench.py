@@ -28,6 +28,9 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # FETCH_SIZE / WRITE_SIZE counters in profiles/dense_c2_hbm_traffic_pmc.txt (scaled by the
 # plain-copy calibration stated there); only reported when that workload is the one timed.
 C2_PASS_TRAFFIC_BYTES = (1070017.4 * 2.0 + 8208.6) * 1024.0
+# HBM bytes per iteration of the sparse workload c3 (both gather launches), from the counters in
+# profiles/csr_c3_hbm_traffic_pmc.txt; None until that file has been measured.
+C3_ITERATION_TRAFFIC_BYTES = None
 EPS = 1e-16
 
 
@@ -134,10 +137,23 @@ def bench_c1(args, torch, nmf, nmf_inputs):
     nmf.nmf_mu_dense(A, m, n, k, W, H, args.steps, EPS)
     t1 = sync_time(torch)
     ms_step = (t1 - t0) * 1e3 / args.steps
-    return {"metric": "MU iterations/s (dense fp32, launch bound)", "value": 1e3 / ms_step, "unit": "iterations/s",
-            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": "c1: dense 256x192, k=4"}}
+    out = {"metric": "MU iterations/s (dense fp32, launch bound)", "value": 1e3 / ms_step, "unit": "iterations/s",
+           "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": "c1: dense 256x192, k=4"},
+           # the whole problem (192 KiB) lives in cache: the iteration is a chain of dependent launches
+           "roofline": {"bound": "launch latency", "achieved": None, "peak": None, "unit": None, "frac": None,
+                        "traffic": None, "launches_per_iteration": 4}}
+    if not args.no_cpu_baseline:
+        from oracle import nmf_oracle as orc
+        Ah = A.cpu().numpy()
+        W0, H0 = (t.numpy() for t in nmf_inputs.init_factors(m, n, k, seed=2001))
+        t0 = time.perf_counter()
+        orc.mu_dense(Ah, W0, H0, 100, EPS)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 100 / dt, "unit": "iterations/s", "cores": orc.num_threads(), "kind": "oracle",
+                               "sample": f"all 100 iterations of the 256x192, k=4 workload in {dt * 1e3:.0f} ms (float64)"}
+    return out
 
 
 def bench_c3(args, torch, nmf, nmf_inputs):
@@ -169,7 +185,23 @@ def bench_c3(args, torch, nmf, nmf_inputs):
     bytes_a = 2 * (8 * nnz + 8 * (m + 1))       # both passes read values, column indices, row pointers
     gbs = bytes_a / (ms_step * 1e-3) / 1e9
     gather = 2 * nnz * k * 4 + bytes_a
-    return {"metric": "MU iterations/s (CSR fp32)", "value": 1e3 / ms_step, "unit": "iterations/s",
+    cpu = None
+    if not args.no_cpu_baseline:
+        # the oracle on the first 1/16 of the rows (same H, a sixteenth of A and W), a few iterations
+        from oracle import nmf_oracle as orc
+        ms_ = m // 16
+        rp = rowptr[:ms_ + 1].cpu().numpy()
+        e1 = int(rp[-1])
+        ci, va = colidx[:e1].cpu().numpy(), vals[:e1].cpu().numpy()
+        W0, H0 = (t.cpu().numpy() for t in nmf_inputs.init_factors(ms_, n, k, seed=2003, device="cuda"))
+        t0 = time.perf_counter()
+        orc.mu_csr(rp, ci, va, ms_, n, W0, H0, 2, EPS)
+        dt = time.perf_counter() - t0
+        cpu = {"value": 2 / dt / 16, "unit": "iterations/s", "cores": orc.num_threads(), "kind": "oracle",
+               "sample": f"2 iterations on the first {ms_} rows ({e1} stored entries, 1/16 of the matrix) in {dt:.1f} s, "
+                         "scaled by 1/16 to the whole matrix (float64)"}
+    out_c3 = {"cpu_baseline": cpu} if cpu else {}
+    return {**out_c3, "metric": "MU iterations/s (CSR fp32)", "value": 1e3 / ms_step, "unit": "iterations/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
             "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
             "config": {"workload": f"c3: CSR {m}x{n}, nnz={nnz}, k={k}", "nnz": nnz},
@@ -178,7 +210,8 @@ def bench_c3(args, torch, nmf, nmf_inputs):
             # (the tables, 128 MiB and 512 MiB here, do not fit the 4 MiB of L2 an XCD has)
             "roofline": {"bound": "hbm", "kernel": "aht_csr_kernel", "achieved": gather / (ms_step * 1e-3) / 1e9,
                          "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": gather / (ms_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "traffic": None, "algorithmic_bytes_per_iteration": gather},
+                         "traffic": C3_ITERATION_TRAFFIC_BYTES if (m, n, k) == (4194304, 1048576, 32) else None,
+                         "algorithmic_bytes_per_iteration": gather},
             "objective": {"residual_fro": obj[-1], "iterations": mon_iters,
                           "ms_more_per_monitored_iteration": mon_extra_ms}}
 
@@ -251,18 +284,37 @@ def bench_c4(args, torch, nmf, nmf_inputs):
     del slot
     log(f"[bench] c4: bare pinned H2D copy {copy_gbs:.1f} GB/s")
     iters = args.steps
+    # one short untimed call: the staging slots and the workspace are allocated by the first call
+    nmf.nmf_mu_ooc(Ah[:2 * batch], 2 * batch, n, k, W[:2 * batch].clone(), H.clone(), 1, EPS, batch, budget)
     t0 = sync_time(torch)
     nmf.nmf_mu_ooc(Ah, m, n, k, W, H, iters, EPS, batch, budget)
     t1 = sync_time(torch)
-    sweeps = iters + 1
+    sweeps = iters + 1                     # the half-iteration skew: one upload of A more than iterations
     gbs = sweeps * m * n * 4 / (t1 - t0) / 1e9
     ms_step = (t1 - t0) * 1e3 / iters
-    return {"metric": "MU iterations/s (dense fp32, A streamed from pinned host memory)", "value": 1e3 / ms_step,
-            "unit": "iterations/s", "n_gpus": 1, "steps": iters, "warmup": 0, "ms_per_step": ms_step,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": f"c4: dense {m}x{n} in pinned host memory, {batch}-row batches, 8 GiB staging budget, "
-                                   f"k={k}, {iters} iterations = {sweeps} uploads of A"},
-            "h2d_gbs_achieved": gbs, "h2d_gbs_bare_copy": copy_gbs, "frac_of_bare_copy": gbs / copy_gbs}
+    out = {"metric": "MU iterations/s (dense fp32, A streamed from pinned host memory)", "value": 1e3 / ms_step,
+           "unit": "iterations/s", "n_gpus": 1, "steps": iters, "warmup": 0, "ms_per_step": ms_step,
+           "ms_per_sweep": (t1 - t0) * 1e3 / sweeps,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"c4: dense {m}x{n} in pinned host memory, {batch}-row batches, 8 GiB staging budget, "
+                                  f"k={k}, {iters} iterations = {sweeps} uploads of A"},
+           "h2d_gbs_achieved": gbs, "h2d_gbs_bare_copy": copy_gbs, "frac_of_bare_copy": gbs / copy_gbs,
+           # bound by the host link: achieved = bytes of A uploaded / time, peak = the bare pinned copy of the
+           # same chunks measured above (PCIe Gen5 x16 is 64 GB/s raw per direction)
+           "roofline": {"bound": "host link", "achieved": gbs, "peak": copy_gbs, "unit": "GB/s", "frac": gbs / copy_gbs,
+                        "traffic": None, "algorithmic_bytes_per_sweep": m * n * 4}}
+    if not args.no_cpu_baseline:
+        from oracle import nmf_oracle as orc
+        Ab = Ah[:batch].numpy()
+        W0, H0 = (t.numpy() for t in nmf_inputs.init_factors(batch, n, k, seed=2004))
+        t0 = time.perf_counter()
+        orc.mu_dense(Ab, W0, H0, 1, EPS)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": 1 / dt / (m // batch), "unit": "iterations/s", "cores": orc.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"1 iteration on one {batch}-row batch of {m // batch} in {dt:.1f} s, scaled to the "
+                                         "whole matrix (float64)"}
+    return out
 
 
 def bench_oom1(args, torch, nmf, nmf_inputs):
@@ -357,11 +409,31 @@ def bench_c5(args, torch, nmf, nmf_inputs):
     t1 = sync_time(torch)
     nruns = len(runs_k)
     per_run_500 = (t1 - t0) / nruns * (500 / iters)
-    return {"metric": "ensemble runs/s (500 MU iterations per run)", "value": 1.0 / per_run_500, "unit": "runs/s",
-            "n_gpus": 1, "steps": iters, "warmup": args.warmup, "ms_per_step": (t1 - t0) * 1e3 / iters,
-            "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-            "config": {"workload": f"c5: dense {m}x{n}, {copies} perturbed copies x k={kmin}..{kmax} = {nruns} runs; "
-                                   f"timed {iters} iterations per run, scaled to 500"}}
+    useful = 4.0 * m * n * sum(runs_k) * iters              # the two products over A, fp32 multiply-adds x 2
+    out = {"metric": "ensemble runs/s (500 MU iterations per run)", "value": 1.0 / per_run_500, "unit": "runs/s",
+           "n_gpus": 1, "steps": iters, "warmup": args.warmup, "ms_per_step": (t1 - t0) * 1e3 / iters,
+           "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+           "config": {"workload": f"c5: dense {m}x{n}, {copies} perturbed copies x k={kmin}..{kmax} = {nruns} runs; "
+                                  f"timed {iters} iterations per run, scaled to 500"},
+           "tflops_useful_fp32": useful / (t1 - t0) / 1e12,
+           # matrix-core bound: every fp32 product is nine bf16 piece products, so the instructions issued
+           # amount to 9 x the useful operations (stacks are padded to 32 or 64 factors on top of that)
+           "roofline": {"bound": "mfma", "achieved": 9 * useful / (t1 - t0) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": 9 * useful / (t1 - t0) / 1e12 / 2500.0, "traffic": None, "instruction": "bf16"}}
+    if not args.no_cpu_baseline:
+        from oracle import nmf_oracle as orc
+        Ah = As[0].cpu().numpy()
+        W0, H0 = (t.numpy() for t in nmf_inputs.init_factors(m, n, 8, seed=2005))
+        t0 = time.perf_counter()
+        orc.mu_dense(Ah, W0, H0, 2, EPS)
+        dt = time.perf_counter() - t0
+        # a run of rank k costs about k / 8 of this one; the ensemble's mean rank is sum(k) / runs
+        scale = (sum(runs_k) / nruns) / 8.0
+        out["cpu_baseline"] = {"value": 1.0 / (dt / 2 * 500 * scale), "unit": "runs/s", "cores": orc.num_threads(),
+                               "kind": "oracle",
+                               "sample": f"2 iterations of one k=8 run in {dt:.1f} s, scaled to 500 iterations and to the "
+                                         f"ensemble's mean rank {sum(runs_k) / nruns:.1f} (float64)"}
+    return out
 
 
 def main():
@@ -374,6 +446,7 @@ def main():
     ap.add_argument("--slots", default="1,2,3,4,8", help="staging slot counts swept by oom1")
     ap.add_argument("--small", action="store_true", help="reduced c3/c4 sizes (debugging)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sub", action="store_true", help="default workload only: leave out the shortened runs of c1, c3, c4, c5")
     ap.add_argument("--calibrate", action="store_true", help="also run one plain device copy of A (counter scaling)")
     ap.add_argument("--kmin", type=int, default=2)
     ap.add_argument("--kmax", type=int, default=16)
@@ -393,6 +466,28 @@ def main():
     fn = {"c1": bench_c1, "c2": bench_c2, "c3": bench_c3, "c3ooc": bench_c3ooc, "c4": bench_c4, "c5": bench_c5, "oom1": bench_oom1,
           "ck": bench_ck}[args.workload]
     out = fn(args, torch, nmf, nmf_inputs)
+    if args.workload == "c2" and not args.no_sub:
+        # The other four configurations, shortened, so that one default run times all five: same entry
+        # points and launch configurations as their own --workload runs, fewer steps.
+        import copy
+        import gc
+        out["sub_results"] = {}
+        for name, steps, warm in (("c1", 200, 20), ("c3", 10, 1), ("c4", 3, 0), ("c5", 10, 1)):
+            gc.collect()
+            torch.cuda.synchronize()
+            nmf.nmf_mu_release()
+            torch.cuda.empty_cache()
+            if hasattr(torch._C, "_host_emptyCache"):
+                torch._C._host_emptyCache()
+            a2 = copy.copy(args)
+            a2.steps, a2.warmup = steps, warm
+            t0 = time.perf_counter()
+            r = {"c1": bench_c1, "c3": bench_c3, "c4": bench_c4, "c5": bench_c5}[name](a2, torch, nmf, nmf_inputs)
+            keep = ("metric", "value", "unit", "steps", "ms_per_step", "ms_per_sweep", "config", "roofline", "cpu_baseline",
+                    "gbs_over_A", "h2d_gbs_achieved", "h2d_gbs_bare_copy", "tflops_useful_fp32")
+            out["sub_results"][name] = {a: r[a] for a in keep if a in r}
+            out["sub_results"][name]["wall_s"] = time.perf_counter() - t0
+            log(f"[bench] {name}: {r['value']:.4g} {r['unit']} ({time.perf_counter() - t0:.1f} s)")
     print(json.dumps(out), flush=True)
 
 
