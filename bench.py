@@ -29,8 +29,8 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # plain-copy calibration stated there); only reported when that workload is the one timed.
 C2_PASS_TRAFFIC_BYTES = (1070017.4 * 2.0 + 8208.6) * 1024.0
 # HBM bytes per iteration of the sparse workload c3 (both gather launches), from the counters in
-# profiles/csr_c3_hbm_traffic_pmc.txt; None until that file has been measured.
-C3_ITERATION_TRAFFIC_BYTES = None
+# profiles/csr_c3_hbm_traffic_pmc.txt (scaled by the plain-copy calibration stated there).
+C3_ITERATION_TRAFFIC_BYTES = (30746040.6 + 30666910.4) * 2.0 * 1024.0 + (131072.0 + 524328.3) * 1024.0
 EPS = 1e-16
 
 
@@ -166,6 +166,13 @@ def bench_c3(args, torch, nmf, nmf_inputs):
     nnz = int(vals.numel())
     W, H = nmf_inputs.init_factors(m, n, k, seed=2003, device="cuda")
     log(f"[bench] c3: CSR {m}x{n}, nnz={nnz} ({nnz / m:.1f} per row), generated in {time.perf_counter() - t0:.1f} s")
+    if args.calibrate:
+        # a plain device copy of known size (reads and writes 4 nnz bytes), for scaling the
+        # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run
+        B = torch.empty_like(vals)
+        B.copy_(vals)
+        torch.cuda.synchronize()
+        del B
     nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, max(args.warmup, 1), EPS)
     t0 = sync_time(torch)
     nmf.nmf_mu_csr(rowptr, colidx, vals, m, n, nnz, k, W, H, args.steps, EPS)
