@@ -24,10 +24,10 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
-# HBM bytes per launch of the streaming pass kernel on the default workload, from the
-# FETCH_SIZE / WRITE_SIZE counters in profiles/dense_c2_hbm_traffic_pmc.txt (scaled by the
+# HBM bytes per launch of the two streaming pass kernels on the default workload (row plan), from
+# the FETCH_SIZE / WRITE_SIZE counters in profiles/dense_c2_hbm_traffic_pmc.txt (scaled by the
 # plain-copy calibration stated there); only reported when that workload is the one timed.
-C2_PASS_TRAFFIC_BYTES = (1070017.4 * 2.0 + 8208.6) * 1024.0
+C2_PASS_TRAFFIC_BYTES = {"wta_pass": (1073360.9 * 2.0 + 8208.6) * 1024.0, "aht_pass": (1101514.4 * 2.0 + 4437.3) * 1024.0}
 # HBM bytes per iteration of the sparse workload c3 (both gather launches), from the counters in
 # profiles/csr_c3_hbm_traffic_pmc.txt (scaled by the plain-copy calibration stated there).
 C3_ITERATION_TRAFFIC_BYTES = (30746040.6 + 30666910.4) * 2.0 * 1024.0 + (131072.0 + 524328.3) * 1024.0
@@ -113,7 +113,7 @@ def bench_c2(args, torch, nmf, nmf_inputs, m=32768, n=16384, k=32, rank=32, tag=
         "kernel_ms": kern, "pass_kernel_ms_back_to_back": alone,
         "roofline": {"bound": "hbm", "kernel": dom, "kernel_ms": timed[dom], "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": ach / HBM_PEAK_GBS,
-                     "traffic": C2_PASS_TRAFFIC_BYTES if (m, n, k, bool(kms[6])) == (32768, 16384, 32, True) else None,
+                     "traffic": C2_PASS_TRAFFIC_BYTES[dom] if (m, n, k, int(kms[6])) == (32768, 16384, 32, 2) else None,
                      "algorithmic_bytes_per_launch": bytes_a},
     }
     # the objective ||A - W H||_F in row tiles (one more streaming pass over A), blocking call

@@ -1627,7 +1627,7 @@ __global__ __launch_bounds__(256, 2) void residual_stream_kernel(const float *__
         const float *tp = A + (i0 < r1 ? i0 : 0) * n + j0;
 #pragma unroll
         for (int v = 0; v < 16; ++v)
-            a[v] = *reinterpret_cast<const f32x2 *>(tp + (int64_t)((v & 3) + 8 * (v >> 2)) * n + lane_off);
+            a[v] = __builtin_nontemporal_load(reinterpret_cast<const f32x2 *>(tp + (int64_t)((v & 3) + 8 * (v >> 2)) * n + lane_off));
     };
 
     double total = 0.0;
