@@ -1162,46 +1162,49 @@ __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__
 
 // ---------------------------------------------------------------------------
 // A H^T pass on the row-major A with the W update fused, k <= 32 ("row plan"; 16-byte aligned
-// A, n % 4 == 0, n < 2^24).  A workgroup of 8 waves owns 64 RG rows of A and W at a time
-// (row blocks blockIdx.x, + gridDim.x, ...): RG row groups of 64 rows, 8 / RG waves per
-// group, which split the 64-column chunks of the block between them; a wave's sub-tile is
-// 32 rows x 64 columns, two per chunk.  MFMA roles: A_op = A elements (32 rows x 16 columns,
-// a lane holds 8 consecutive columns of one row, cut into bf16 pieces in registers), B_op =
-// the piece planes of H^T (16 columns x 32 factors: the planes the H update writes for its
-// new H), so the sums are the exact-piece sums of the W^T A pass, and like there a matrix
-// accumulator runs for at most 32 products deep (8 chunks) before it is added, in rounded
-// fp32, to the wave's totals.  An operand layout with lanes down the rows would make every
-// lane of a load touch its own cache line, so A is loaded coalesced (a wave instruction =
-// 4 rows x 256 contiguous bytes, non-temporal) and turned through a wave-private 8 KiB tile
-// of LDS (16-byte chunks swizzled by row, conflict free both ways; no barrier: only the
-// wave itself touches its tile).  The planes of a chunk (48 registers) serve both row
-// tiles.  Every row block starts its walk over the columns at another chunk (17 x block
+// A, n % 4 == 0, n < 2^24).  A workgroup of 8 waves owns 32 R rows of A and W at a time
+// (row blocks blockIdx.x, + gridDim.x, ...); the waves split the 64-column chunks of the
+// block between them, and a wave's sub-tile is 32 rows x 64 columns, R per chunk.  MFMA
+// roles: A_op = A elements (32 rows x 16 columns, a lane holds 8 consecutive columns of one
+// row, cut into bf16 pieces in registers), B_op = the piece planes of H^T (16 columns x 32
+// factors: the planes the H update writes for its new H; the 48 registers of a chunk serve
+// all R row tiles), so the sums are the exact-piece sums of the W^T A pass, and like there a
+// matrix accumulator runs for at most 32 products deep (8 chunks) before it is added, in
+// rounded fp32, to totals: here totals in LDS shared by the wave pairs (w, w + 4), because
+// R accumulator tiles and R total tiles do not fit a wave's registers beside the planes.
+// An operand layout with lanes down the rows would make every lane of a load touch its own
+// cache line, so A is loaded coalesced (a wave instruction = 4 rows x 256 contiguous bytes,
+// non-temporal) and turned through a wave-private 8 KiB tile of LDS (16-byte chunks
+// swizzled by row, conflict free both ways; no barrier: only the wave itself touches its
+// tile).  Every row block starts its walk over the columns at another chunk (17 x block
 // index): launched in step on the same columns, the workgroups would crowd the same memory
 // channels (0.338 against 0.318 ms for the bare loads on 32768 x 16384).
+// LDS: 64 KiB of staging tiles + 16 R KiB of totals, dynamic (above the 64 KiB a static
+// array may have; a workgroup may use all 160 KiB of a compute unit).
 //
-// Epilogue per row block: the sums of a row group's waves are added through LDS in wave
-// order; W <- W * Q / (W GH + eps) for the block's rows with GH = H H^T (k x k, complete);
-// then from the new rows in LDS: their bf16 piece planes (operand of the next W^T A pass),
-// this workgroup's share of W^T W (fp32 matrix instruction, one tile set per workgroup in
-// gout, which the next W^T A pass adds up in groups) and, with dpart, its share of
-// <A H^T, W_new> in double.
+// Epilogue per row block: the four totals are added in order; W <- W * Q / (W GH + eps) for
+// the block's rows with GH = H H^T (k x k, complete); then from the new rows in LDS: their
+// bf16 piece planes (operand of the next W^T A pass), this workgroup's share of W^T W (fp32
+// matrix instruction, one tile set per workgroup in gout, which the next W^T A pass adds up
+// in groups) and, with dpart, its share of <A H^T, W_new> in double.
 // mode 1: no pass and no update, only the planes and the Gram share of W as it is (the
 // same summation order, so that a run cut into two calls gives the same bits).  mode 2: the
 // whole pass with the stores to W and its planes left out (timing).
 // ---------------------------------------------------------------------------
-template <int RG>
+extern __shared__ float aht_rows_lds[];
+template <int R>
 __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
     const float *__restrict__ A, const u32x4 *__restrict__ planesH, const float *__restrict__ GH,
     float *W, u32x4 *__restrict__ planesW, float *__restrict__ gout,
     double *__restrict__ dpart, int64_t rows, int64_t n, int k, float eps, int mode, BlockMap bm)
 {
-    constexpr int NW = 8, NWC = NW / RG, RB = 64 * RG, LDW = 33;
+    constexpr int NW = 8, RB = 32 * R, LDW = 33;
     constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
-    __shared__ float lds[NW * 2048];          // all of the 64 KiB a workgroup can have
+    float *lds = aht_rows_lds;             // staging tiles: 8 x 2048 floats
+    float *T = aht_rows_lds + NW * 2048;   // totals of the four wave pairs: 4 x (R x 1024) floats
     double *dsum = reinterpret_cast<double *>(lds + 16368);      // used after the last row block only
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int rg = w / NWC, wc = w % NWC;
     float *stg = lds + w * 2048;
     const int jj = lane & 31, half = lane >> 5;
     const unsigned rowb = (unsigned)(n * 4);
@@ -1211,33 +1214,25 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
     // coalesced loads: instruction u of a sub-tile covers rows 4u .. 4u+3, lane = (row, 16-byte chunk)
     const int lrow = lane >> 4, lch = lane & 15;
     const unsigned loff = (unsigned)lrow * rowb + (unsigned)lch * 16;
-
-    // epilogue arrays (they alias the staging tiles; barriers separate the phases): the sums of
-    // row group g in accumulator layout at lds + g * NWC * 2048 + (rt * 16 + v) * 64 + lane
-    float *Ws = lds + 2048;               // old rows   [RB][LDW]
-    float *Gs = Ws + 128 * LDW;           // H H^T      [32][LDW]
-    float *Wn = lds + 10240;              // new rows   [RB][LDW]
-
+    // epilogue arrays (they alias the staging tiles; barriers separate the phases)
+    float *Ws = lds;                      // old rows   [RB][LDW]
+    float *Wn = lds + 4352;               // new rows   [RB][LDW]
+    float *Gs = lds + 8704;               // H H^T      [32][LDW]
     f32x16 gacc = {0};                    // this wave's share of W^T W over all row blocks
     double dacc = 0.0;
+    const int rounds = (int)((nchunks + 63) >> 6);   // a round = up to 8 chunks per wave
 
     for (int64_t blk = blockIdx.x; blk < nblocks; blk += gridDim.x) {
         const int64_t i0 = blk * RB;
         if (mode != 1) {
             const int64_t rot = (blk * 17) % nchunks;
-            const int64_t ib = i0 + 64 * rg;            // first row of this wave's row group
-            f32x16 acc[2], tot[2];
+            f32x16 acc[R];
 #pragma unroll
-            for (int r = 0; r < 2; ++r) acc[r] = tot[r] = f32x16{0};
-            struct Stage {
-                u32x4 a[8];
-            };
-            auto phys = [&](int64_t ch) {
-                const int64_t c = ch + rot;
-                return c >= nchunks ? c - nchunks : c;
-            };
+            for (int r = 0; r < R; ++r) acc[r] = f32x16{0};
+            struct Stage { u32x4 a[8]; };
+            auto phys = [&](int64_t ch) { const int64_t c = ch + rot; return c >= nchunks ? c - nchunks : c; };
             auto load_stage = [&](Stage &s, int64_t chl, int rt) {
-                const int64_t rbase = ib + 32 * rt;
+                const int64_t rbase = i0 + 32 * rt;
                 int64_t av = rows - rbase;                  // rows of this sub-tile that exist
                 av = av < 0 ? 0 : (av > 32 ? 32 : av);
                 if (chl >= nchunks) av = 0;                 // past the last chunk: nothing is loaded
@@ -1262,8 +1257,7 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
                     for (int pl = 0; pl < 3; ++pl)
-                        bp[s][pl] = __builtin_amdgcn_raw_buffer_load_b128(
-                            rp, (unsigned)((((2 * s + half) * 3 + pl) * 32 + jj) * 16), 0, 0);
+                        bp[s][pl] = __builtin_amdgcn_raw_buffer_load_b128(rp, (unsigned)((((2 * s + half) * 3 + pl) * 32 + jj) * 16), 0, 0);
             };
             auto to_lds = [&](const Stage &s) {
 #pragma unroll
@@ -1280,17 +1274,13 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     const f32x4 x1 = *reinterpret_cast<const f32x4 *>(stg + jj * 64 + (((c0 + 1) ^ (jj & 15)) << 2));
                     u32x4 at[3];
                     unsigned h0, m0, l0, h1, m1, l1;
-                    split3(x0.x, h0, m0, l0);
-                    split3(x0.y, h1, m1, l1);
+                    split3(x0.x, h0, m0, l0); split3(x0.y, h1, m1, l1);
                     at[0][0] = pack2(h0, h1), at[1][0] = pack2(m0, m1), at[2][0] = pack2(l0, l1);
-                    split3(x0.z, h0, m0, l0);
-                    split3(x0.w, h1, m1, l1);
+                    split3(x0.z, h0, m0, l0); split3(x0.w, h1, m1, l1);
                     at[0][1] = pack2(h0, h1), at[1][1] = pack2(m0, m1), at[2][1] = pack2(l0, l1);
-                    split3(x1.x, h0, m0, l0);
-                    split3(x1.y, h1, m1, l1);
+                    split3(x1.x, h0, m0, l0); split3(x1.y, h1, m1, l1);
                     at[0][2] = pack2(h0, h1), at[1][2] = pack2(m0, m1), at[2][2] = pack2(l0, l1);
-                    split3(x1.z, h0, m0, l0);
-                    split3(x1.w, h1, m1, l1);
+                    split3(x1.z, h0, m0, l0); split3(x1.w, h1, m1, l1);
                     at[0][3] = pack2(h0, h1), at[1][3] = pack2(m0, m1), at[2][3] = pack2(l0, l1);
                     // the nine piece products, smallest first
                     a = mfma_bf16(at[2], bp[s][2], a);
@@ -1304,56 +1294,58 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     a = mfma_bf16(at[0], bp[s][0], a);
                 }
             };
-            // Sub-tiles in the order (chunk, row tile); the loads of the next one are requested
-            // as soon as the current one has gone to LDS.
-            int since = 0;
+            // Sub-tiles in the order (chunk, row tile); the loads of the next one are requested as soon
+            // as the current one has gone to LDS.  After every round (8 chunks = 32 products deep) the
+            // matrix accumulators are added, in rounded fp32, to totals in LDS that the waves w and w + 4
+            // share: first the lower four waves, then the upper four, a barrier after each.
             Stage s0;
-            int64_t ch = wc;
-            load_stage(s0, ch, 0);
-            for (; ch < nchunks; ch += NWC) {
-                load_b(ch);
-                to_lds(s0);
-                __builtin_amdgcn_sched_barrier(0);
-                load_stage(s0, ch, 1);
-                __builtin_amdgcn_sched_barrier(0);
-                compute(acc[0]);
-                __builtin_amdgcn_sched_barrier(0);
-                to_lds(s0);
-                __builtin_amdgcn_sched_barrier(0);
-                load_stage(s0, ch + NWC, 0);
-                __builtin_amdgcn_sched_barrier(0);
-                compute(acc[1]);
-                __builtin_amdgcn_sched_barrier(0);
-                if (++since == 8) {
-                    since = 0;
+            load_stage(s0, w, 0);
+            float *Tp = T + (w & 3) * (R * 1024);
+            for (int r = 0; r < rounds; ++r) {
+                for (int t = 0; t < 8; ++t) {
+                    const int64_t ch = w + 8 * (int64_t)(8 * r + t);
+                    if (ch >= nchunks) break;        // this wave has no more chunks (loads already requested nothing)
+                    load_b(ch);
 #pragma unroll
-                    for (int r = 0; r < 2; ++r) {
-                        tot[r] += acc[r];
-                        acc[r] = f32x16{0};
+                    for (int rt = 0; rt < R; ++rt) {
+                        to_lds(s0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (rt + 1 < R) load_stage(s0, ch, rt + 1);
+                        else load_stage(s0, ch + 8, 0);
+                        __builtin_amdgcn_sched_barrier(0);
+                        compute(acc[rt]);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+                if (w < 4) {
+#pragma unroll
+                    for (int rt = 0; rt < R; ++rt) {
+                        float old[16];
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) old[v] = r ? Tp[(rt * 16 + v) * 64 + lane] : 0.f;
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) { Tp[(rt * 16 + v) * 64 + lane] = old[v] + acc[rt][v]; acc[rt][v] = 0.f; }
+                    }
+                }
+                __syncthreads();
+                if (w >= 4) {
+#pragma unroll
+                    for (int rt = 0; rt < R; ++rt) {
+                        float old[16];
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) old[v] = Tp[(rt * 16 + v) * 64 + lane];
+#pragma unroll
+                        for (int v = 0; v < 16; ++v) { Tp[(rt * 16 + v) * 64 + lane] = old[v] + acc[rt][v]; acc[rt][v] = 0.f; }
+                    }
+                }
+                __syncthreads();
             }
-#pragma unroll
-            for (int r = 0; r < 2; ++r) tot[r] += acc[r];
-
-            // ---- the waves of each row group, added in wave order ----
-            // a wave's own tile first (nobody else touches it), then the sums in place
-#pragma unroll
-            for (int rt = 0; rt < 2; ++rt)
-#pragma unroll
-                for (int v = 0; v < 16; ++v) stg[(rt * 16 + v) * 64 + lane] = tot[rt][v];
+            // the four pairs' totals, added in order, in place
+            for (int e = tid; e < R * 1024; e += 64 * NW)
+                T[e] = ((T[e] + T[R * 1024 + e]) + T[2 * R * 1024 + e]) + T[3 * R * 1024 + e];
             __syncthreads();
-            for (int e = tid; e < RG * 2048; e += 64 * NW) {
-                float *p0 = lds + (e >> 11) * (NWC * 2048) + (e & 2047);
-                float t = p0[0];
-#pragma unroll
-                for (int ww = 1; ww < NWC; ++ww) t += p0[ww * 2048];
-                p0[0] = t;
-            }
-            __syncthreads();                       // the other tiles change hands
         }
-
-        // ---- H H^T from the partial tile sets, and the block's rows of W ----
+        // ---- H H^T and the block's rows of W ----
         if (mode != 1) {
             for (int e = tid; e < 32 * 32; e += 64 * NW) {
                 const int c = e >> 5, d = e & 31;
@@ -1386,8 +1378,7 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     }
                     const float den = ((d0 + d1) + (d2 + d3)) + eps;
                     const int r = i & 31;
-                    const float q = lds[(i >> 6) * (NWC * 2048) +
-                                        ((((i >> 5) & 1) * 16 + ((r & 3) | ((r >> 3) << 2))) * 64) + 32 * ((r >> 2) & 1) + c];
+                    const float q = T[((i >> 5) * 16 + ((r & 3) | ((r >> 3) << 2))) * 64 + 32 * ((r >> 2) & 1) + c];
                     wn = wr[c] * q / den;
                     if (mode == 0) W[(i0 + i) * k + c] = wn;
                     dacc += (double)q * (double)wn;
@@ -1422,16 +1413,11 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
         }
         __syncthreads();                           // LDS goes back to the staging tiles
     }
-
     if (dpart) {
         for (int off = 32; off > 0; off >>= 1) dacc += __shfl_xor(dacc, off);
         if (lane == 0) dsum[w] = dacc;
         __syncthreads();
-        if (tid == 0) {
-            double t = 0.0;
-            for (int i = 0; i < NW; ++i) t += dsum[i];
-            dpart[blockIdx.x] = t;
-        }
+        if (tid == 0) { double t = 0.0; for (int i = 0; i < NW; ++i) t += dsum[i]; dpart[blockIdx.x] = t; }
     }
     // this workgroup's share of W^T W: the eight waves' tiles added in wave order
 #pragma unroll
@@ -2114,14 +2100,32 @@ bool aht_rows_ok(const float *A, int64_t m, int64_t n, int k)
     return k <= 32 && vec_ok(A, n) && n < ((int64_t)1 << 24) && (m >= 4096 || m * n <= ((int64_t)1 << 22));
 }
 
-static int aht_rows_groups(int64_t rows) { return (rows + 127) / 128 >= 192 ? 2 : 1; }
+// row tiles per workgroup: 128-row blocks when they fill the chip, else 64-row blocks
+static int aht_rows_tiles(int64_t rows) { return (rows + 127) / 128 >= 192 ? 4 : 2; }
 
 int aht_rows_blocks(int64_t rows)
 {
-    const int64_t rb = 64 * aht_rows_groups(rows);
+    const int64_t rb = 32 * aht_rows_tiles(rows);
     int64_t b = (rows + rb - 1) / rb;
     if (b > kFinMaxBlocks) b = kFinMaxBlocks;
     return (int)b;
+}
+
+template <int R>
+static hipError_t aht_rows_launch(dim3 grid, hipStream_t st, const float *A, const u32x4 *ph, const float *GH, float *W,
+                                  u32x4 *pw, float *gout, double *dpart, int64_t rows, int64_t n, int k, float eps,
+                                  int mode, const BlockMap &bm)
+{
+    constexpr int kLdsBytes = (8 * 2048 + 4 * R * 1024) * (int)sizeof(float);
+    static bool raised = false;      // more dynamic LDS than the default limit: asked for once per process
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&aht_rows_kernel<R>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((aht_rows_kernel<R>), grid, dim3(512), kLdsBytes, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
+    return hipGetLastError();
 }
 
 hipError_t launch_aht_rows(const float *A, int64_t rows, int64_t n, int k, const void *planesH,
@@ -2133,15 +2137,12 @@ hipError_t launch_aht_rows(const float *A, int64_t rows, int64_t n, int k, const
     BlockMap bm;
     if (map) bm = *map;
     else bm.on = 0;
-    const dim3 grid((unsigned)aht_rows_blocks(rows)), block(512);
+    const dim3 grid((unsigned)aht_rows_blocks(rows));
     const u32x4 *ph = static_cast<const u32x4 *>(planesH);
     u32x4 *pw = static_cast<u32x4 *>(planesW);
     const int mode = gram_only ? 1 : (dry ? 2 : 0);
-    if (aht_rows_groups(rows) == 2)
-        hipLaunchKernelGGL((aht_rows_kernel<2>), grid, block, 0, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
-    else
-        hipLaunchKernelGGL((aht_rows_kernel<1>), grid, block, 0, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
-    return hipGetLastError();
+    if (aht_rows_tiles(rows) == 4) return aht_rows_launch<4>(grid, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
+    return aht_rows_launch<2>(grid, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
 }
 
 hipError_t launch_sum_f64(const double *in, int64_t count, double *out, hipStream_t st)
