@@ -380,6 +380,16 @@ int sliced_ftx(const Sliced &e, const float *F, int64_t rows, int k, const float
     const int kSlice = wta_planes_only_width(X, cols);
     const int splits = wta_splits(rows, cols, kSlice);
     const int64_t rps = wta_rows_per_split(rows, splits);
+    const int nslices = (k + 63) / 64;
+    if (kSlice == 64 && k > 64) {
+        // all slices in one launch each: the slices of a tile of X run side by side and share its bytes
+        if ((size_t)splits * 64 * (size_t)cols * nslices > e.ppart_elems || planes_bytes(rows) * nslices > e.planes_cap)
+            return fail(NMF_EHIP, "internal: sliced scratch too small%s");
+        NMF_HIP(launch_split_planes_slices(F, rows, k, e.planes, st));
+        NMF_HIP(launch_wta_pass_slices(X, rows, cols, k, e.planes, e.ppart, splits, rps, st));
+        NMF_HIP(launch_sum_partials_slices(e.ppart, splits, k, cols, out, st, accumulate));
+        return NMF_OK;
+    }
     if ((size_t)splits * kSlice * (size_t)cols > e.ppart_elems || planes_bytes(rows) > e.planes_cap)
         return fail(NMF_EHIP, "internal: sliced scratch too small%s");
     for (int c0 = 0; c0 < k; c0 += kSlice) {
@@ -414,11 +424,12 @@ SlicedDense carve_sliced_dense(void *ws, int64_t m, int64_t n, int k, size_t *by
     SlicedDense p;
     cv.take<unsigned>(64);
     const int64_t big = m > n ? m : n;
-    p.e.planes_cap = planes_bytes(max3<int64_t>(m, n, k));
-    p.e.ppart_elems = sliced_ppart_elems(max3<int64_t>(m, n, k));
+    const size_t nslices = (size_t)(k + 63) / 64;
+    p.e.planes_cap = planes_bytes(max3<int64_t>(m, n, k)) * nslices;
+    p.e.ppart_elems = sliced_ppart_elems(max3<int64_t>(m, n, k)) * nslices;
     p.e.planes = cv.take<char>(p.e.planes_cap);
     // X is one of A (m x n), W (m x k), H (k x n) or a transpose of those
-    p.e.ppart = cv.take<float>(sliced_ppart_elems(max3<int64_t>(m, n, k)));
+    p.e.ppart = cv.take<float>(p.e.ppart_elems);
     p.At = cv.take<float>((size_t)m * n);
     p.Wt = cv.take<float>((size_t)k * m);
     p.Ht = cv.take<float>((size_t)n * k);
@@ -474,10 +485,11 @@ SlicedOoc carve_sliced_ooc(void *ws, int64_t rb, int64_t n, int k, size_t *bytes
     Carve cv(ws);
     SlicedOoc p;
     cv.take<unsigned>(64);
-    p.e.planes_cap = planes_bytes(max3<int64_t>(rb, n, k));
-    p.e.ppart_elems = sliced_ppart_elems(max3<int64_t>(rb, n, k));
+    const size_t nslices = (size_t)(k + 63) / 64;
+    p.e.planes_cap = planes_bytes(max3<int64_t>(rb, n, k)) * nslices;
+    p.e.ppart_elems = sliced_ppart_elems(max3<int64_t>(rb, n, k)) * nslices;
     p.e.planes = cv.take<char>(p.e.planes_cap);
-    p.e.ppart = cv.take<float>(sliced_ppart_elems(max3<int64_t>(rb, n, k)));
+    p.e.ppart = cv.take<float>(p.e.ppart_elems);
     p.Abt = cv.take<float>((size_t)n * rb);
     p.Wbt = cv.take<float>((size_t)k * rb);
     p.num_b = cv.take<float>((size_t)k * rb);

@@ -408,10 +408,15 @@ __global__ __launch_bounds__(64 * kWtaWaves, OCC) void wta_pass_kernel(const flo
 // planes[(g * 3 + p) * kp + c] = the eight bf16 p-th pieces (p = 0: h, 1: m, 2: l)
 // of X[8 g .. 8 g + 7][c0 + c], c < kp; rows beyond `rows` and columns beyond kc are zero.
 // ---------------------------------------------------------------------------
+// blockIdx.y = slice: columns c0 + kp * slice onwards (at most kp of the k left), planes + slice * slice_planes.
 __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restrict__ X, int64_t rows,
                                                            int64_t ld, int64_t c0, int k, int kp,
-                                                           u32x4 *__restrict__ planes)
+                                                           u32x4 *__restrict__ planes, int64_t slice_planes)
 {
+    c0 += (int64_t)kp * blockIdx.y;
+    k -= kp * (int)blockIdx.y;
+    if (k > kp) k = kp;
+    planes += (int64_t)blockIdx.y * slice_planes;
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t g = t / kp;
     const int c = (int)(t % kp);
@@ -662,27 +667,50 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
 // against 531 us for waves interleaved down the rows of one 64-column slab; the matrix
 // pipe is busy 70 % of the cycles at the 1.7 GHz the chip sustains under this load.
 // ---------------------------------------------------------------------------
+// Several 64-factor slices of a wider factor in one launch (SLICES; ranks above 64): a
+// one-dimensional grid whose workgroup L stands for (tile, slice) with the slices of one
+// tile of A (slab x row split) 8 workgroups apart, i.e. on the same XCD at about the same
+// time, so that A comes from HBM once and from that XCD's L2 for the other slices (loaded
+// with the default cache policy then; a single slice streams A non-temporally).  Slice z
+// reads planes + z * slice_planes and writes ppart + z * slice_ppart; it holds
+// min(64, ktotal - 64 z) factors.
+template <bool SLICES>
 __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kernel(
     const float *__restrict__ A, const u32x4 *__restrict__ planes, float *__restrict__ ppart,
     int64_t rows, int64_t n, int k, int64_t rps, int accumulate,
-    const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum)
+    const float *__restrict__ gtiles, int nsets, float *__restrict__ gsum,
+    int gx, int gy, int nslices, int64_t slice_planes, int64_t slice_ppart)
 {
     typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
     typedef float f32x2 __attribute__((ext_vector_type(2)));
     constexpr int KP = 64;
     constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
+    constexpr int kPolicy = SLICES ? 0 : kStreamLoad;
     __shared__ float tot[kWtaWaves * kTotFloats];
-    if (gtiles) sum_tile_groups(gtiles, nsets, k, gsum);
+    int bx = blockIdx.x, by = blockIdx.y;
+    if (SLICES) {
+        const int L = blockIdx.x, within = L >> 3;
+        const int z = within % nslices;
+        const int t = (within / nslices) * 8 + (L & 7);
+        if (t >= gx * gy) return;
+        bx = t % gx;
+        by = t / gx;
+        planes += (int64_t)z * slice_planes;
+        ppart += (int64_t)z * slice_ppart;
+        k = (k - 64 * z < 64) ? k - 64 * z : 64;
+    } else if (gtiles) {
+        sum_tile_groups(gtiles, nsets, k, gsum);
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
     float *mytot = tot + w * kTotFloats;   // register (t, q, v) of this lane at ((2 t + q) * 16 + v) * 64 + lane
     tot_clear(mytot, lane);
     const int jj = lane & 31, half = lane >> 5;
-    const int64_t jw = (int64_t)blockIdx.x * 256 + 64 * w;
+    const int64_t jw = (int64_t)bx * 256 + 64 * w;
     if (jw >= n) return;     // no barrier below: a wave wholly past the edge has nothing to do
     const int64_t colr = jw + 2 * jj;
     const int64_t col = colr < n ? colr : 0;   // lanes past the edge read valid data that is never stored
-    const int64_t r0 = (int64_t)blockIdx.y * rps;
+    const int64_t r0 = (int64_t)by * rps;
     const int64_t r1 = (r0 + rps < rows) ? r0 + rps : rows;
     const unsigned rowb = (unsigned)(n * 4);
     const unsigned loff = (unsigned)(half * 8) * rowb + (unsigned)col * 4;
@@ -710,7 +738,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kerne
         const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
             const_cast<u32x4 *>(planes + (ng ? g : 0) * 3 * KP), 0, (int)(ng * 3 * KP * 16), kRsrcFlags);
 #pragma unroll
-        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b64(ra, loff + r * rowb, 0, kStreamLoad);
+        for (int r = 0; r < 8; ++r) s.a[r] = __builtin_amdgcn_raw_buffer_load_b64(ra, loff + r * rowb, 0, kPolicy);
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -780,7 +808,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kerne
     }
 
     if (colr < n) {
-        float *dst = ppart + (int64_t)blockIdx.y * k * n + colr;
+        float *dst = ppart + (int64_t)by * k * n + colr;
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
@@ -1749,10 +1777,16 @@ __global__ __launch_bounds__(256) void objective_kernel(const double *__restrict
 }
 
 // P = sum over the row splits of the partial W^T A results (test entry point only).
+// blockIdx.y = slice of 64 factors (ranks above 64): partials at ppart + slice * slice_ppart, `count`
+// floats of P per full slice, count_last for the last one.
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float *__restrict__ ppart,
                                                            int splits, int64_t count,
-                                                           float *__restrict__ P, int accumulate)
+                                                           float *__restrict__ P, int accumulate,
+                                                           int64_t slice_ppart, int64_t count_last)
 {
+    ppart += (int64_t)blockIdx.y * slice_ppart;
+    P += (int64_t)blockIdx.y * count;
+    if (blockIdx.y == gridDim.y - 1) count = count_last;
     for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < count; e += (int64_t)gridDim.x * 256) {
         float s = 0.f;
         for (int t = 0; t < splits; ++t) s += ppart[(int64_t)t * count + e];
@@ -1883,7 +1917,43 @@ hipError_t launch_split_planes_slice(const float *X, int64_t rows, int64_t ld, i
     const int kp = kc <= 32 ? 32 : 64;
     const int64_t threads = ((rows + 7) / 8) * kp;
     hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st, X,
-                       rows, ld, c0, kc, kp, static_cast<u32x4 *>(planes));
+                       rows, ld, c0, kc, kp, static_cast<u32x4 *>(planes), (int64_t)0);
+    return hipGetLastError();
+}
+
+hipError_t launch_split_planes_slices(const float *X, int64_t rows, int k, void *planes, hipStream_t st)
+{
+    const int nslices = (k + 63) / 64;
+    const int64_t threads = ((rows + 7) / 8) * 64;
+    hipLaunchKernelGGL(split_planes_kernel, dim3((unsigned)((threads + 255) / 256), (unsigned)nslices), dim3(256), 0, st, X,
+                       rows, (int64_t)k, (int64_t)0, k, 64, static_cast<u32x4 *>(planes), (int64_t)(planes_bytes(rows) / 16));
+    return hipGetLastError();
+}
+
+hipError_t launch_wta_pass_slices(const float *A, int64_t rows, int64_t n, int k, const void *planes, float *ppart,
+                                  int splits, int64_t rps, hipStream_t st)
+{
+    if (!vec_ok(A, n) || n >= ((int64_t)1 << 25) || rps % 16 || k <= 64) return hipErrorInvalidValue;
+    const int nslices = (k + 63) / 64;
+    const int gx = (int)((n + 255) / 256), gy = splits;
+    const int64_t tiles8 = ((int64_t)gx * gy + 7) / 8 * 8;
+    hipLaunchKernelGGL((wta_pass_split64_wide_kernel<true>), dim3((unsigned)(tiles8 * nslices)), dim3(64 * kWtaWaves), 0, st, A,
+                       static_cast<const u32x4 *>(planes), ppart, rows, n, k, rps, 0, static_cast<const float *>(nullptr), 0,
+                       static_cast<float *>(nullptr), gx, gy, nslices, (int64_t)(planes_bytes(rows) / 16),
+                       (int64_t)splits * 64 * n);
+    return hipGetLastError();
+}
+
+hipError_t launch_sum_partials_slices(const float *ppart, int splits, int k, int64_t cols, float *P, hipStream_t st,
+                                      bool accumulate)
+{
+    const int nslices = (k + 63) / 64;
+    const int64_t count = 64 * cols, count_last = (int64_t)(k - 64 * (nslices - 1)) * cols;
+    int64_t b = (count + 255) / 256;
+    if (b > 4096) b = 4096;
+    // the partials of slice z hold splits x (factors of z) x cols floats, packed for that slice's width
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b, (unsigned)nslices), dim3(256), 0, st, ppart, splits, count, P,
+                       accumulate ? 1 : 0, (int64_t)splits * 64 * cols, count_last);
     return hipGetLastError();
 }
 
@@ -1933,8 +2003,9 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
                 if (e != hipSuccess) return e;
             }
             const dim3 grid256((unsigned)((n + 255) / 256), (unsigned)splits);
-            hipLaunchKernelGGL(wta_pass_split64_wide_kernel, grid256, dim3(64 * kWtaWaves), 0, st, A,
-                               static_cast<const u32x4 *>(planes), ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
+            hipLaunchKernelGGL((wta_pass_split64_wide_kernel<false>), grid256, dim3(64 * kWtaWaves), 0, st, A,
+                               static_cast<const u32x4 *>(planes), ppart, rows, n, k, rps, acc, gtiles, nsets, gsum,
+                               0, 0, 1, (int64_t)0, (int64_t)0);
         } else {
             if (!W) return hipErrorInvalidValue;   // this kernel reads the factor itself, not its planes
             wta_dispatch<2>(vec, grid, st, A, W, ppart, rows, n, k, rps, acc, gtiles, nsets, gsum);
@@ -1989,7 +2060,8 @@ hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, fl
 {
     int64_t b = (count + 255) / 256;
     if (b > 4096) b = 4096;
-    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b), dim3(256), 0, st, ppart, splits, count, P, accumulate ? 1 : 0);
+    hipLaunchKernelGGL(sum_partials_kernel, dim3((unsigned)b), dim3(256), 0, st, ppart, splits, count, P, accumulate ? 1 : 0,
+                       (int64_t)0, count);
     return hipGetLastError();
 }
 

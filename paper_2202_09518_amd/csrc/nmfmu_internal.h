@@ -67,6 +67,16 @@ hipError_t launch_wta_pass(const float *A, int64_t rows, int64_t n, int k, const
 // gtiles (optional): nsets sets of partial Gram tiles for rank k that the first workgroups of
 // the pass add up in groups of kGramGroup into gsum (gram_groups(nsets) sets).
 inline int gram_groups(int nsets) { return (nsets + kGramGroup - 1) / kGramGroup; }
+// Ranks above 64, all ceil(k / 64) slices of 64 factors in one launch each: planes of every slice of X
+// (rows x k; slice z at planes + z * planes_bytes(rows)), the pass over A for every slice (aligned A,
+// n % 4 == 0; partials of slice z at ppart + z * splits * 64 * n, packed for that slice's width), and
+// P (k x cols) (+)= the sums over the splits.  The slices of one tile of A run side by side, so A is
+// fetched from HBM about once per product.
+hipError_t launch_split_planes_slices(const float *X, int64_t rows, int k, void *planes, hipStream_t st);
+hipError_t launch_wta_pass_slices(const float *A, int64_t rows, int64_t n, int k, const void *planes, float *ppart,
+                                  int splits, int64_t rps, hipStream_t st);
+hipError_t launch_sum_partials_slices(const float *ppart, int splits, int k, int64_t cols, float *P, hipStream_t st,
+                                      bool accumulate = false);
 // P[e] (+)= sum_s ppart[s][e], e < count.
 hipError_t launch_sum_partials(const float *ppart, int splits, int64_t count, float *P,
                                hipStream_t st, bool accumulate = false);
