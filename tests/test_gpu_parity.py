@@ -132,6 +132,35 @@ def test_mu_dense_one_iteration(m, n, k):
     check(Wg, Hg, Wr, Hr, TOL1)
 
 
+# The row plan (k <= 32, m >= 4096 or a small problem): ragged rows and columns, more row blocks
+# than workgroups (the kernel then walks several blocks), 64-row and 128-row blocks, ranks off the
+# tile sizes.  k = 33 and a misaligned view take the other plans on the same shapes.
+@pytest.mark.parametrize("m,n,k,iters", [
+    (4100, 1028, 17, 2), (5000, 260, 32, 2), (40000, 128, 8, 2), (4097, 68, 1, 1), (33000, 1200, 32, 1),
+    (24600, 4, 3, 2), (8192, 8256, 32, 1), (4100, 1028, 33, 1),
+])
+def test_row_plan_shapes(m, n, k, iters):
+    A, W, H = case(m, n, k, 300 + k)
+    Wg, Hg = run_dense(A, W, H, iters)
+    Wr, Hr = orc.mu_dense(A, W, H, iters, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, TOL1 * iters)
+
+
+def test_row_plan_zero_rows_and_columns():
+    """All-zero rows and columns of A inside and at the edges of row blocks and column chunks."""
+    A, W, H = case(4200, 520, 16, 310)
+    A[0, :] = 0
+    A[127:130, :] = 0
+    A[4199, :] = 0
+    A[:, 63:66] = 0
+    A[:, 519] = 0
+    Wg, Hg = run_dense(A, W, H, 3)
+    Wr, Hr = orc.mu_dense(A, W, H, 3, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, 3 * TOL1)
+    assert (Wg[0] == 0).all() and (Wg[128] == 0).all() and (Wg[4199] == 0).all()
+    assert (Hg[:, 64] == 0).all() and (Hg[:, 519] == 0).all()
+
+
 def config1():
     A = nmf_inputs.dense_planted(256, 192, 4, seed=1001, noise="add", lo=0.0, hi=0.01).numpy()
     W, H = nmf_inputs.init_factors(256, 192, 4, seed=2001)
