@@ -1565,15 +1565,16 @@ __global__ __launch_bounds__(256) void residual_kernel(const float *__restrict__
 // owns 64 of the columns and walks down all the rows of the split, a lane 2 consecutive
 // columns.  Once per wave its slab of H is cut into bf16 pieces (B_op: lane l holds factors
 // 8 (l / 32) .. + 7 of 16 for column l % 32), kept in registers for every row tile.  Per
-// 32-row tile a wave loads the rows of W (A_op: lane l holds 8 consecutive factors of row
-// l % 32), cuts them into pieces, forms the two 32 x 32 tiles of W H with 2 x 9 instructions
-// each, and subtracts them from the tile of A, loaded in the accumulator layout (lane l,
-// register v: row (v % 4) + 4 (l / 32) + 8 (v / 4), its 2 columns: 8-byte loads, 1 KiB
-// contiguous per row over the workgroup).  The next tile of A is requested before the
-// current tile's arithmetic and the next tile's rows of W once the current ones are cut.
-// One double per workgroup.  Measured on the 32768 x 16384, k = 32 case the matrix
-// instructions' time adds to the streaming time instead of hiding under it (six of the nine
-// products take 53 us less), which leaves the kernel at 4.4 TB/s.
+// 32-row tile a wave forms the two 32 x 32 tiles of W H with 2 x 9 instructions each from
+// pieces of the rows of W (A_op: lane l holds 8 consecutive factors of row l % 32) that the
+// workgroup makes once for its four waves (wave w cuts tile w of every group of
+// four tiles into LDS, double buffered, one barrier per group), and subtracts them from the
+// tile of A, loaded in the accumulator layout (lane l, register v: row (v % 4) + 4 (l / 32) +
+// 8 (v / 4), its 2 columns: 8-byte loads, 1 KiB contiguous per row over the workgroup).  The
+// next tile of A is requested before the current tile's arithmetic, the rows of W two groups
+// ahead.  One double per workgroup.  On the 32768 x 16384, k = 32 case the kernel takes
+// 0.37 ms on random operands and 0.31 ms, the time of its loads alone, on all-zero ones:
+// what is left is the chip's power limit under matrix work and streaming together.
 // ---------------------------------------------------------------------------
 template <int KSTEPS>
 __global__ __launch_bounds__(256, 2) void residual_stream_kernel(const float *__restrict__ A,
@@ -1645,33 +1646,47 @@ __global__ __launch_bounds__(256, 2) void residual_stream_kernel(const float *__
     };
 
     double total = 0.0;
-    // one tile, its A already requested: cut W, request the next tile's W, products, differences
-    auto tile = [&](const ATile &a, int64_t i0, bool valid) {
-        u32x4 wp[KSTEPS][3];
+    // The four waves walk the same row tiles, so the pieces of a tile of W are made once per
+    // workgroup: of every group of four tiles wave w cuts tile w and stores it in LDS in
+    // operand order (entry [tile][step * 3 + piece][lane], 16 bytes each), while the group
+    // before it is consumed from the other buffer; one barrier per group.
+    __shared__ u32x4 wlds[2][4][KSTEPS * 3][64];
+    auto cut_store = [&](int buf) {
 #pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
+        for (int s = 0; s < KSTEPS; ++s) {
+            u32x4 wp[3];
 #pragma unroll
             for (int pr = 0; pr < 4; ++pr) {
                 unsigned h0, m0, l0, h1, m1, l1;
                 split3(wv[s][pr >> 1][(2 * pr) & 3], h0, m0, l0);
                 split3(wv[s][pr >> 1][(2 * pr + 1) & 3], h1, m1, l1);
-                wp[s][0][pr] = pack2(h0, h1);
-                wp[s][1][pr] = pack2(m0, m1);
-                wp[s][2][pr] = pack2(l0, l1);
+                wp[0][pr] = pack2(h0, h1);
+                wp[1][pr] = pack2(m0, m1);
+                wp[2][pr] = pack2(l0, l1);
             }
-        load_w(i0 + 32);
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc) wlds[buf][w][s * 3 + pc][lane] = wp[pc];
+        }
+    };
+    // one tile, its A already requested: pieces of W from LDS, products, differences.  The two
+    // 32-column halves are two chains of 9 KSTEPS instructions one after the other, so the
+    // differences of the first half can issue under the products of the second.
+    auto tile = [&](const ATile &a, int buf, int t, bool valid) {
+        u32x4 wp[KSTEPS][3];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s)
+#pragma unroll
+            for (int pc = 0; pc < 3; ++pc) wp[s][pc] = wlds[buf][t][s * 3 + pc][lane];
         f32x16 acc[2];
         acc[0] = f32x16{0};
         acc[1] = f32x16{0};
         constexpr int PW[9] = {2, 2, 1, 2, 1, 0, 1, 0, 0}, PH[9] = {2, 1, 2, 0, 1, 2, 0, 1, 0};   // smallest first
 #pragma unroll
-        for (int e = 0; e < 9; ++e)
+        for (int q = 0; q < 2; ++q)
 #pragma unroll
-            for (int s = 0; s < KSTEPS; ++s)
+            for (int e = 0; e < 9; ++e)
 #pragma unroll
-                for (int q = 0; q < 2; ++q) acc[q] = mfma_bf16(wp[s][PW[e]], hp[s][q][PH[e]], acc[q]);
-        __builtin_amdgcn_sched_barrier(0);
+                for (int s = 0; s < KSTEPS; ++s) acc[q] = mfma_bf16(wp[s][PW[e]], hp[s][q][PH[e]], acc[q]);
         float local = 0.f;      // 32 terms per lane in fp32, double across tiles
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
@@ -1681,19 +1696,33 @@ __global__ __launch_bounds__(256, 2) void residual_stream_kernel(const float *__
         }
         total += valid ? (double)local : 0.0;
     };
-    // two tiles per trip; the second may lie past the split: it is then tile 0 again, and
-    // its sum is dropped
+    // four tiles per trip (every wave of the workgroup makes the same trips: r0 and r1 are the
+    // workgroup's); a tile past the split is tile 0 again, and its sum is dropped
     ATile a0, a1;
     int64_t i = r0;
-    load_w(i);
+    load_w(i + 32 * w);
+    cut_store(0);
+    load_w(i + 128 + 32 * w);
     load_a(a0, i);
-    for (; i < r1; i += 64) {
+    __syncthreads();
+    int buf = 0;
+    for (; i < r1; i += 128) {
+        cut_store(buf ^ 1);
+        load_w(i + 256 + 32 * w);
         load_a(a1, i + 32);
         __builtin_amdgcn_sched_barrier(0);
-        tile(a0, i, true);
+        tile(a0, buf, 0, true);
         load_a(a0, i + 64);
         __builtin_amdgcn_sched_barrier(0);
-        tile(a1, i + 32, i + 32 < r1);
+        tile(a1, buf, 1, i + 32 < r1);
+        load_a(a1, i + 96);
+        __builtin_amdgcn_sched_barrier(0);
+        tile(a0, buf, 2, i + 64 < r1);
+        load_a(a0, i + 128);
+        __builtin_amdgcn_sched_barrier(0);
+        tile(a1, buf, 3, i + 96 < r1);
+        __syncthreads();    // the group's buffer is free, the next group's is written
+        buf ^= 1;
     }
     if (!colok) total = 0.0;   // such lanes subtracted a zero product from columns of other lanes
     for (int off = 32; off > 0; off >>= 1) total += __shfl_xor(total, off);

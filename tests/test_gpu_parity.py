@@ -344,10 +344,12 @@ def test_dense_random_shapes_two_iterations(m, n, k):
 
 # ---- objective and tolerance-driven run --------------------------------------------
 
-# the last six take the streaming kernel: whole 32-row tiles (with up to 31 rows left to the
-# general one), ragged and single column slabs, both factor step counts, fewer tiles than waves
+# the last ten take the streaming kernel: whole 32-row tiles (with up to 31 rows left to the
+# general one), ragged and single column slabs, both factor step counts, fewer tiles than waves,
+# and 5, 6, 7 and 9 tiles per row split (the kernel takes them in groups of four)
 @pytest.mark.parametrize("m,n,k", SHAPES + [(4096, 2048, 32), (1000, 520, 16), (31, 64, 32), (32, 4, 16),
-                                            (4128, 68, 16), (163, 8200, 32), (8192, 64, 32)])
+                                            (4128, 68, 16), (163, 8200, 32), (8192, 64, 32),
+                                            (2591, 8200, 32), (4608, 8200, 16), (98304, 64, 16), (114705, 64, 32)])
 def test_residual_dense(m, n, k):
     A, W, H = case(m, n, k, 32)
     got = nmf.nmf_residual_dense(dev(A), m, n, k, dev(W), dev(H))
