@@ -83,12 +83,15 @@ const char *nmf_last_error(void);
  *   W, H   device, in/out
  *   iters  >= 0;  eps >= 0 and finite
  * Asynchronous on `stream`.  Three plans, chosen per call; they give the same
- * iteration and differ in low-order bits.  Row plan (k <= 32, 16-byte aligned
- * A, n % 4 == 0, n < 2^24, and m >= 4096 or m n <= 2^22): both products stream
+ * iteration and differ in low-order bits.  Row plan (16-byte aligned A,
+ * n % 4 == 0, n < 2^24, and m >= 4096 or m n <= 2^22): both products stream
  * the row-major A, the W update is fused into the A H^T pass; workspace kind 4.
- * Mirrored plan (other shapes, if the workspace can hold a second copy of A):
- * A is transposed once per call and A^T is streamed for the A H^T product;
- * workspace kind 0.  Small plan otherwise: a direct A H^T kernel on A (lanes
+ * It comes first for k <= 32.  Mirrored plan (33 <= k <= 64, and shapes the
+ * row plan does not serve, if the workspace can hold a second copy of A): A is
+ * transposed once per call and A^T is streamed for the A H^T product;
+ * workspace kind 0.  Without room for that copy: the row plan for
+ * 33 <= k <= 64 where it applies (its A H^T pass is about a fifth slower than
+ * the mirrored one), else the small plan, a direct A H^T kernel on A (lanes
  * down the rows: slower); workspace kind 4.
  * Ranks NMF_MU_MAX_K < k <= NMF_MU_MAX_K_SLICED run the same iteration with every
  * product written as F^T X (a reduction over the rows of two row-major

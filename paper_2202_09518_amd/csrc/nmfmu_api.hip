@@ -182,11 +182,21 @@ DensePlan carve_dense(void *ws, int64_t m, int64_t n, int k, bool mirrored)
     return p;
 }
 
+// Which plan runs.  Up to 32 factors the row plan comes first wherever its kernel applies.  From 33
+// to 64 factors its A H^T pass is slower than the W^T A kernel on a transposed copy (622 against
+// 525 us on 32768 x 16384, 167 against 132 us on 16384 x 8192), so there the mirrored plan comes
+// first and the row plan serves when the workspace cannot hold the copy.
+static bool rows_plan_first(const float *A, int64_t m, int64_t n, int k) { return k <= 32 && aht_rows_ok(A, m, n, k); }
+static bool rows_plan_runs(const float *A, int64_t m, int64_t n, int k, bool mirrored)
+{
+    return aht_rows_ok(A, m, n, k) && (k <= 32 || !mirrored);
+}
+
 // Workspace for a dense run: the mirrored plan if it can be had, else the small one.
 int dense_workspace(const float *A, int64_t m, int64_t n, int k, void **ws, bool *mirrored)
 {
     const size_t big = dense_bytes(m, n, k, true), small = dense_bytes(m, n, k, false);
-    if (aht_rows_ok(A, m, n, k)) {     // the row plan streams A itself for both products
+    if (rows_plan_first(A, m, n, k)) {     // the row plan streams A itself for both products
         *mirrored = false;
         return ensure_workspace(small, ws);
     }
@@ -228,12 +238,12 @@ int dense_body(const float *A, int64_t m, int64_t n, int k, float *W, float *H, 
     // counts follow the rank actually run; the partial buffer holds the largest case.
     const int s1 = wta_splits(m, n, k), s2 = wta_splits(n, m, k);
     const int64_t rps1 = wta_rows_per_split(m, s1), rps2 = wta_rows_per_split(n, s2);
-    if (aht_rows_ok(A, m, n, k)) {
-        // Row plan (k <= 32): both products stream the row-major A.  The W^T A pass reads the piece
+    if (rows_plan_runs(A, m, n, k, p.mirrored)) {
+        // Row plan: both products stream the row-major A.  The W^T A pass reads the piece
         // planes of W and, on the side, adds the tile sets of W^T W up in groups; the H update writes
         // the planes of H^T and the tile sets of H H^T, which a small launch adds up; the A H^T pass
         // with the fused W update writes the planes of the new W and the tile sets of its W^T W.
-        const int nbw = aht_rows_blocks(m), nbh = factor_update_blocks(n);
+        const int nbw = aht_rows_blocks(m, k), nbh = factor_update_blocks(n);
         const int ngw = gram_groups(nbw);
         // planes and W^T W of the W handed in, with the summation order of an updating launch
         NMF_HIP(launch_aht_rows(nullptr, m, n, k, nullptr, nullptr, W, p.planes, c.gwp, eps, st, true));
@@ -788,7 +798,7 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float 
                 sum[j] += ms;
             }
         for (int j = 0; j < NK; ++j) kernel_ms[j] = (float)(sum[j] / iters);
-        kernel_ms[NK] = aht_rows_ok(A, m, n, k) ? 2.f : (mirrored ? 1.f : 0.f);
+        kernel_ms[NK] = rows_plan_runs(A, m, n, k, mirrored) ? 2.f : (mirrored ? 1.f : 0.f);
         kernel_ms[NK + 1] = kernel_ms[NK + 2] = 0.f;
     }
     // The pass kernels once more, `reps` launches back to back between two events: the
@@ -798,7 +808,7 @@ int nmf_mu_dense_profile(const float *A, int64_t m, int64_t n, int32_t k, float 
         const int reps = 20;
         const int s1 = wta_splits(m, n, k), s2 = wta_splits(n, m, k);
         const int64_t rps1 = wta_rows_per_split(m, s1), rps2 = wta_rows_per_split(n, s2);
-        const bool rows_plan = aht_rows_ok(A, m, n, k);
+        const bool rows_plan = rows_plan_runs(A, m, n, k, mirrored);
         const Common &c = p.c;
         for (int which = 0; which < ((mirrored || rows_plan) ? 2 : 1) && rc == NMF_OK; ++which) {
             if (which == 0) (void)launch_split_planes(W, m, k, p.planes, st);
@@ -942,7 +952,11 @@ static int ooc_run(const float *A_host, int64_t m, int64_t n, int32_t k, float *
     const int64_t nb = (m + batch_rows - 1) / batch_rows;
     // monitored run: the W updates' shares of <A H^T, W> (one per workgroup and batch), ||A_b||^2 per
     // batch and its scratch, ||A||^2, one objective value per iteration
-    const int64_t bpb = aht_pass_blocks(batch_rows);
+    // The W update of a batch: the streaming row kernel where it applies (staging slots are aligned,
+    // so that is a matter of n, k and the batch height), else the direct kernel.
+    const bool use_rows = aht_rows_ok(nullptr, batch_rows, n, k);
+    auto w_blocks = [&](int64_t rows) { return use_rows ? (int64_t)aht_rows_blocks(rows, k) : aht_pass_blocks(rows); };
+    const int64_t bpb = w_blocks(batch_rows);
     const size_t mon_bytes = objective_host
         ? align_up((size_t)(nb * bpb) * sizeof(double)) + align_up((size_t)nb * sizeof(double)) +
           align_up(4097 * sizeof(double)) + align_up((size_t)iters * sizeof(double))
@@ -955,6 +969,7 @@ static int ooc_run(const float *A_host, int64_t m, int64_t n, int32_t k, float *
     const int64_t rps = wta_rows_per_split(batch_rows, splits);
     float *ppart = cv.take<float>((size_t)splits * k * n);
     void *planes = cv.take<char>(planes_bytes(batch_rows));
+    void *planes_ht = cv.take<char>(planes_bytes(n));      // row kernel: piece planes of H^T
     double *dpart = nullptr, *normb = nullptr, *normA2 = nullptr, *obj = nullptr;
     if (objective_host) {
         dpart = cv.take<double>((size_t)(nb * bpb));
@@ -997,10 +1012,15 @@ static int ooc_run(const float *A_host, int64_t m, int64_t n, int32_t k, float *
             NMF_HIP(hipEventRecord(g.ev_copied[slot], g.copy_stream));
             NMF_HIP(hipStreamWaitEvent(st, g.ev_copied[slot], 0));
             if (dpart && s == 0) NMF_HIP(launch_sumsq(Ab, rb * n, normA2 + 1, normb + b, st));
-            if (s > 0)
-                NMF_HIP(launch_aht_pass(Ab, rb, n, k, H, c.gh, W + i0 * k, eps, st, dpart ? dpart + b * bpb : nullptr));
+            if (s > 0) {
+                if (use_rows)    // also leaves the piece planes of the batch's new rows for the pass below
+                    NMF_HIP(launch_aht_rows(Ab, rb, n, k, planes_ht, c.gh, W + i0 * k, planes, c.gwp, eps, st, false, nullptr,
+                                            dpart ? dpart + b * bpb : nullptr));
+                else
+                    NMF_HIP(launch_aht_pass(Ab, rb, n, k, H, c.gh, W + i0 * k, eps, st, dpart ? dpart + b * bpb : nullptr));
+            }
             if (s < iters)
-                NMF_HIP(launch_wta_pass(Ab, rb, n, k, W + i0 * k, planes, false, ppart, splits, rps, b > 0, st));
+                NMF_HIP(launch_wta_pass(Ab, rb, n, k, W + i0 * k, planes, use_rows && s > 0, ppart, splits, rps, b > 0, st));
             NMF_HIP(hipEventRecord(g.ev_freed[slot], st));
         }
         if (dpart && s == 0) NMF_HIP(launch_sum_f64(normb, nb, normA2, st));
@@ -1010,15 +1030,16 @@ static int ooc_run(const float *A_host, int64_t m, int64_t n, int32_t k, float *
             // leaves the tail of its segment untouched, so its workgroups are counted, not bpb),
             // H H^T of the H they used, W^T W of the W they left
             const int64_t last_rows = m - (nb - 1) * batch_rows;
-            if (aht_pass_blocks(last_rows) != bpb) {
+            if (w_blocks(last_rows) != bpb) {
                 // close the gap so that the shares are one contiguous run
-                NMF_HIP(hipMemsetAsync(dpart + (nb - 1) * bpb + aht_pass_blocks(last_rows), 0,
-                                       (size_t)(bpb - aht_pass_blocks(last_rows)) * sizeof(double), st));
+                NMF_HIP(hipMemsetAsync(dpart + (nb - 1) * bpb + w_blocks(last_rows), 0,
+                                       (size_t)(bpb - w_blocks(last_rows)) * sizeof(double), st));
             }
             NMF_HIP(launch_objective(dpart, (int)(nb * bpb), c.gw, c.gh, k, normA2, obj + (s - 1), st));
         }
         if (s < iters) {
-            NMF_HIP(launch_factor_update(H, nullptr, ppart, splits, c.gw, nullptr, 0, nullptr, k, n, eps, st));
+            NMF_HIP(launch_factor_update(H, nullptr, ppart, splits, c.gw, nullptr, 0, nullptr, k, n, eps, st, nullptr,
+                                         use_rows ? planes_ht : nullptr));
             NMF_HIP(launch_gram_h(H, k, n, c.gh, c.gpart, c.counters, st));
         }
     }
@@ -1407,14 +1428,15 @@ int nmf_mu_dense_tol(const float *A, int64_t m, int64_t n, int32_t k, float *W, 
     const size_t extra = residual_scratch_bytes(m, n) + align_up((size_t)kFinMaxBlocks * sizeof(double)) +
                          align_up(4097 * sizeof(double)) + kAlign;
     const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
-    const bool rows_plan = aht_rows_ok(A, m, n, k);
-    if (!rows_plan && ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK))) {
+    if (!rows_plan_first(A, m, n, k) &&
+        ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK))) {
         mirrored = true;
     } else {
         (void)hipGetLastError();
         if (int rc = ensure_workspace(small, &ws)) return rc;
     }
     ws = g.ws;
+    const bool rows_plan = rows_plan_runs(A, m, n, k, mirrored);
     const bool fast = mirrored || rows_plan;   // plans whose W update leaves the objective's terms behind
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
     Carve cv(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
@@ -1480,14 +1502,15 @@ int nmf_mu_dense_monitor(const float *A, int64_t m, int64_t n, int32_t k, float 
     const size_t big = dense_bytes(m, n, k, true) + extra, small = dense_bytes(m, n, k, false) + extra;
     void *ws = nullptr;
     bool mirrored = false;
-    const bool rows_plan = aht_rows_ok(A, m, n, k);
-    if (!rows_plan && ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK))) {
+    if (!rows_plan_first(A, m, n, k) &&
+        ((g.ws && g.ws_bytes >= big) || (g.ws_owned && ensure_workspace(big, &ws) == NMF_OK))) {
         mirrored = true;
     } else {
         (void)hipGetLastError();
         if (int rc = ensure_workspace(small, &ws)) return rc;
     }
     ws = g.ws;
+    const bool rows_plan = rows_plan_runs(A, m, n, k, mirrored);
     const DensePlan p = carve_dense(ws, m, n, k, mirrored);
     Carve cv(static_cast<char *>(ws) + dense_bytes(m, n, k, mirrored));
     Monitor mon;

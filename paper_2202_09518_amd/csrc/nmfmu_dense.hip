@@ -14,7 +14,7 @@
 //   aht_rows_kernel : A H^T on the row-major A (coalesced loads turned through
 //       LDS) with the W update, the planes and the Gram tiles of the new W fused
 //   aht_pass_kernel : the older direct A H^T kernel (lanes down the rows), for
-//       shapes and ranks the others do not serve, and for the streamed batches
+//       shapes the others do not serve (unaligned A, short wide matrices)
 //   gram_kernel, gram_sum_kernel, residual_*_kernel, objective_kernel : the small rest.
 // For k <= 64 and aligned A the products are exact: fp32 operands cut into three
 // bf16 pieces each, nine piece products per term on v_mfma_f32_32x32x16_bf16 with
@@ -1189,8 +1189,8 @@ __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__
 }
 
 // ---------------------------------------------------------------------------
-// A H^T pass on the row-major A with the W update fused, k <= 32 ("row plan"; 16-byte aligned
-// A, n % 4 == 0, n < 2^24).  A workgroup of 8 waves owns 32 R rows of A and W at a time
+// A H^T pass on the row-major A with the W update fused, k <= 32 KT ("row plan"; 16-byte aligned
+// A, n % 4 == 0, n < 2^24; the text below describes KT = 1, the end of it what KT = 2 changes).  A workgroup of 8 waves owns 32 R rows of A and W at a time
 // (row blocks blockIdx.x, + gridDim.x, ...); the waves split the 64-column chunks of the
 // block between them, and a wave's sub-tile is 32 rows x 64 columns, R per chunk.  MFMA
 // roles: A_op = A elements (32 rows x 16 columns, a lane holds 8 consecutive columns of one
@@ -1215,21 +1215,26 @@ __global__ __launch_bounds__(512) void aht_pass_kernel(const float *__restrict__
 // bf16 piece planes (operand of the next W^T A pass), this workgroup's share of W^T W (fp32
 // matrix instruction, one tile set per workgroup in gout, which the next W^T A pass adds up
 // in groups) and, with dpart, its share of <A H^T, W_new> in double.
+// KT = 2 (33 <= k <= 64): planes of 64 factor slots (96 registers per chunk), every cut of A
+// feeds two accumulator chains, R = 2 (four accumulator tiles), 65-float rows in the epilogue,
+// and the block's four tiles of W^T W are added to running tiles in LDS (wave w: tile w % 4
+// over half w / 4 of the block's rows) instead of living in registers across row blocks.
 // mode 1: no pass and no update, only the planes and the Gram share of W as it is (the
 // same summation order, so that a run cut into two calls gives the same bits).  mode 2: the
 // whole pass with the stores to W and its planes left out (timing).
 // ---------------------------------------------------------------------------
 extern __shared__ float aht_rows_lds[];
-template <int R>
+template <int R, int KT>
 __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
     const float *__restrict__ A, const u32x4 *__restrict__ planesH, const float *__restrict__ GH,
     float *W, u32x4 *__restrict__ planesW, float *__restrict__ gout,
     double *__restrict__ dpart, int64_t rows, int64_t n, int k, float eps, int mode, BlockMap bm)
 {
-    constexpr int NW = 8, RB = 32 * R, LDW = 33;
+    constexpr int NW = 8, RB = 32 * R, KP = 32 * KT, LDW = KP + 1, RT = R * KT * 1024;
     constexpr int kRsrcFlags = 0x00020000;   // raw buffer, 32-bit data format (gfx9 family)
     float *lds = aht_rows_lds;             // staging tiles: 8 x 2048 floats
-    float *T = aht_rows_lds + NW * 2048;   // totals of the four wave pairs: 4 x (R x 1024) floats
+    float *T = aht_rows_lds + NW * 2048;   // totals of the four wave pairs: 4 x (R x KT x 1024) floats
+    float *Grun = T + 4 * RT;              // KT = 2: this workgroup's W^T W over its row blocks, 4 tiles
     double *dsum = reinterpret_cast<double *>(lds + 16368);      // used after the last row block only
     const int tid = threadIdx.x, lane = tid & 63;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -1244,9 +1249,12 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
     const unsigned loff = (unsigned)lrow * rowb + (unsigned)lch * 16;
     // epilogue arrays (they alias the staging tiles; barriers separate the phases)
     float *Ws = lds;                      // old rows   [RB][LDW]
-    float *Wn = lds + 4352;               // new rows   [RB][LDW]
-    float *Gs = lds + 8704;               // H H^T      [32][LDW]
-    f32x16 gacc = {0};                    // this wave's share of W^T W over all row blocks
+    float *Wn = lds + RB * LDW;           // new rows   [RB][LDW]
+    float *Gs = lds + 2 * RB * LDW;       // H H^T      [KP][LDW]
+    static_assert(2 * RB * LDW + KP * LDW <= 16368, "epilogue arrays must fit the staging tiles");
+    f32x16 gacc = {0};                    // KT = 1: this wave's share of W^T W over all row blocks
+    if (KT == 2)
+        for (int e = tid; e < 4096; e += 64 * NW) Grun[e] = 0.f;   // first read after many barriers
     double dacc = 0.0;
     const int rounds = (int)((nchunks + 63) >> 6);   // a round = up to 8 chunks per wave
 
@@ -1254,9 +1262,11 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
         const int64_t i0 = blk * RB;
         if (mode != 1) {
             const int64_t rot = (blk * 17) % nchunks;
-            f32x16 acc[R];
+            f32x16 acc[R][KT];
 #pragma unroll
-            for (int r = 0; r < R; ++r) acc[r] = f32x16{0};
+            for (int r = 0; r < R; ++r)
+#pragma unroll
+                for (int ft = 0; ft < KT; ++ft) acc[r][ft] = f32x16{0};
             struct Stage { u32x4 a[8]; };
             auto phys = [&](int64_t ch) { const int64_t c = ch + rot; return c >= nchunks ? c - nchunks : c; };
             auto load_stage = [&](Stage &s, int64_t chl, int rt) {
@@ -1274,18 +1284,21 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                 for (int u = 0; u < 8; ++u)
                     s.a[u] = __builtin_amdgcn_raw_buffer_load_b128(ra, lo + (unsigned)(4 * u) * rowb, 0, kStreamLoad);
             };
-            u32x4 bp[4][3];
+            u32x4 bp[4][3][KT];
             auto load_b = [&](int64_t chl) {
                 const int64_t g = phys(chl) * 8;
                 int64_t ng = ngroups - g;                   // 8-column groups of planes that exist
                 ng = ng < 0 ? 0 : (ng > 8 ? 8 : ng);
                 const __amdgpu_buffer_rsrc_t rp = __builtin_amdgcn_make_buffer_rsrc(
-                    const_cast<u32x4 *>(planesH + (ng ? g : 0) * 3 * 32), 0, (int)(ng * 3 * 32 * 16), kRsrcFlags);
+                    const_cast<u32x4 *>(planesH + (ng ? g : 0) * 3 * KP), 0, (int)(ng * 3 * KP * 16), kRsrcFlags);
 #pragma unroll
                 for (int s = 0; s < 4; ++s)
 #pragma unroll
                     for (int pl = 0; pl < 3; ++pl)
-                        bp[s][pl] = __builtin_amdgcn_raw_buffer_load_b128(rp, (unsigned)((((2 * s + half) * 3 + pl) * 32 + jj) * 16), 0, 0);
+#pragma unroll
+                        for (int ft = 0; ft < KT; ++ft)
+                            bp[s][pl][ft] = __builtin_amdgcn_raw_buffer_load_b128(
+                                rp, (unsigned)((((2 * s + half) * 3 + pl) * KP + 32 * ft + jj) * 16), 0, 0);
             };
             auto to_lds = [&](const Stage &s) {
 #pragma unroll
@@ -1294,7 +1307,7 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     *reinterpret_cast<f32x4 *>(stg + row * 64 + ((lch ^ (row & 15)) << 2)) = __builtin_bit_cast(f32x4, s.a[u]);
                 }
             };
-            auto compute = [&](f32x16 &a) {
+            auto compute = [&](f32x16 (&a)[KT]) {
 #pragma unroll
                 for (int s = 0; s < 4; ++s) {
                     const int c0 = 4 * s + 2 * half;
@@ -1310,16 +1323,12 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     at[0][2] = pack2(h0, h1), at[1][2] = pack2(m0, m1), at[2][2] = pack2(l0, l1);
                     split3(x1.z, h0, m0, l0); split3(x1.w, h1, m1, l1);
                     at[0][3] = pack2(h0, h1), at[1][3] = pack2(m0, m1), at[2][3] = pack2(l0, l1);
-                    // the nine piece products, smallest first
-                    a = mfma_bf16(at[2], bp[s][2], a);
-                    a = mfma_bf16(at[2], bp[s][1], a);
-                    a = mfma_bf16(at[1], bp[s][2], a);
-                    a = mfma_bf16(at[2], bp[s][0], a);
-                    a = mfma_bf16(at[1], bp[s][1], a);
-                    a = mfma_bf16(at[0], bp[s][2], a);
-                    a = mfma_bf16(at[1], bp[s][0], a);
-                    a = mfma_bf16(at[0], bp[s][1], a);
-                    a = mfma_bf16(at[0], bp[s][0], a);
+                    // the nine piece products, smallest first (per 32-factor tile: independent chains)
+                    constexpr int PA[9] = {2, 2, 1, 2, 1, 0, 1, 0, 0}, PB[9] = {2, 1, 2, 0, 1, 2, 0, 1, 0};
+#pragma unroll
+                    for (int e = 0; e < 9; ++e)
+#pragma unroll
+                        for (int ft = 0; ft < KT; ++ft) a[ft] = mfma_bf16(at[PA[e]], bp[s][PB[e]][ft], a[ft]);
                 }
             };
             // Sub-tiles in the order (chunk, row tile); the loads of the next one are requested as soon
@@ -1328,7 +1337,7 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
             // share: first the lower four waves, then the upper four, a barrier after each.
             Stage s0;
             load_stage(s0, w, 0);
-            float *Tp = T + (w & 3) * (R * 1024);
+            float *Tp = T + (w & 3) * RT;
             for (int r = 0; r < rounds; ++r) {
                 for (int t = 0; t < 8; ++t) {
                     const int64_t ch = w + 8 * (int64_t)(8 * r + t);
@@ -1347,58 +1356,64 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                 }
                 if (w < 4) {
 #pragma unroll
-                    for (int rt = 0; rt < R; ++rt) {
+                    for (int rt = 0; rt < R * KT; ++rt) {
                         float old[16];
 #pragma unroll
                         for (int v = 0; v < 16; ++v) old[v] = r ? Tp[(rt * 16 + v) * 64 + lane] : 0.f;
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) { Tp[(rt * 16 + v) * 64 + lane] = old[v] + acc[rt][v]; acc[rt][v] = 0.f; }
+                        for (int v = 0; v < 16; ++v) {
+                            Tp[(rt * 16 + v) * 64 + lane] = old[v] + acc[rt / KT][rt % KT][v];
+                            acc[rt / KT][rt % KT][v] = 0.f;
+                        }
                     }
                 }
                 __syncthreads();
                 if (w >= 4) {
 #pragma unroll
-                    for (int rt = 0; rt < R; ++rt) {
+                    for (int rt = 0; rt < R * KT; ++rt) {
                         float old[16];
 #pragma unroll
                         for (int v = 0; v < 16; ++v) old[v] = Tp[(rt * 16 + v) * 64 + lane];
 #pragma unroll
-                        for (int v = 0; v < 16; ++v) { Tp[(rt * 16 + v) * 64 + lane] = old[v] + acc[rt][v]; acc[rt][v] = 0.f; }
+                        for (int v = 0; v < 16; ++v) {
+                            Tp[(rt * 16 + v) * 64 + lane] = old[v] + acc[rt / KT][rt % KT][v];
+                            acc[rt / KT][rt % KT][v] = 0.f;
+                        }
                     }
                 }
                 __syncthreads();
             }
             // the four pairs' totals, added in order, in place
-            for (int e = tid; e < R * 1024; e += 64 * NW)
-                T[e] = ((T[e] + T[R * 1024 + e]) + T[2 * R * 1024 + e]) + T[3 * R * 1024 + e];
+            for (int e = tid; e < RT; e += 64 * NW)
+                T[e] = ((T[e] + T[RT + e]) + T[2 * RT + e]) + T[3 * RT + e];
             __syncthreads();
         }
         // ---- H H^T and the block's rows of W ----
         if (mode != 1) {
-            for (int e = tid; e < 32 * 32; e += 64 * NW) {
-                const int c = e >> 5, d = e & 31;
+            for (int e = tid; e < KP * KP; e += 64 * NW) {
+                const int c = e / KP, d = e % KP;
                 // stacked independent runs: factor indices of different runs do not interact
                 const bool in = c < k && d < k && (!bm.on || bm.id[c] == bm.id[d]);
                 const float v = GH[in ? c * k + d : 0];
                 Gs[c * LDW + d] = in ? v : 0.f;
             }
         }
-        for (int e = tid; e < RB * 32; e += 64 * NW) {
-            const int i = e >> 5, c = e & 31;
+        for (int e = tid; e < RB * KP; e += 64 * NW) {
+            const int i = e / KP, c = e % KP;
             const bool in = i0 + i < rows && c < k;
             const float v = W[in ? (i0 + i) * k + c : 0];
             (mode != 1 ? Ws : Wn)[i * LDW + c] = in ? v : 0.f;
         }
         __syncthreads();
         if (mode != 1) {
-            for (int e = tid; e < RB * 32; e += 64 * NW) {
-                const int i = e >> 5, c = e & 31;
+            for (int e = tid; e < RB * KP; e += 64 * NW) {
+                const int i = e / KP, c = e % KP;
                 float wn = 0.f;
                 if (i0 + i < rows && c < k) {
                     float d0 = 0.f, d1 = 0.f, d2 = 0.f, d3 = 0.f;
                     const float *wr = Ws + i * LDW;
 #pragma unroll
-                    for (int d = 0; d < 32; d += 4) {
+                    for (int d = 0; d < KP; d += 4) {
                         d0 += wr[d + 0] * Gs[(d + 0) * LDW + c];
                         d1 += wr[d + 1] * Gs[(d + 1) * LDW + c];
                         d2 += wr[d + 2] * Gs[(d + 2) * LDW + c];
@@ -1406,7 +1421,7 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     }
                     const float den = ((d0 + d1) + (d2 + d3)) + eps;
                     const int r = i & 31;
-                    const float q = T[((i >> 5) * 16 + ((r & 3) | ((r >> 3) << 2))) * 64 + 32 * ((r >> 2) & 1) + c];
+                    const float q = T[(((i >> 5) * KT + (c >> 5)) * 16 + ((r & 3) | ((r >> 3) << 2))) * 64 + 32 * ((r >> 2) & 1) + (c & 31)];
                     wn = wr[c] * q / den;
                     if (mode == 0) W[(i0 + i) * k + c] = wn;
                     dacc += (double)q * (double)wn;
@@ -1416,8 +1431,8 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
             __syncthreads();
         }
         // ---- by-products of the new rows: piece planes, Gram share ----
-        if (tid < (RB / 8) * 32) {
-            const int gl = tid >> 5, c = tid & 31;
+        if (tid < (RB / 8) * KP) {
+            const int gl = tid / KP, c = tid % KP;
             const int64_t grow = (i0 >> 3) + gl;
             if (grow * 8 < rows && mode != 2) {
                 u32x4 o[3];
@@ -1431,13 +1446,30 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     o[2][pr] = pack2(ll[0], ll[1]);
                 }
 #pragma unroll
-                for (int pl = 0; pl < 3; ++pl) planesW[(grow * 3 + pl) * 32 + c] = o[pl];
+                for (int pl = 0; pl < 3; ++pl) planesW[(grow * 3 + pl) * KP + c] = o[pl];
             }
         }
+        if (KT == 1) {
 #pragma unroll
-        for (int q = 0; q < RB / 16; ++q) {
-            const float va = Wn[(2 * (w + NW * q) + half) * LDW + jj];
-            gacc = mfma32(va, va, gacc);
+            for (int q = 0; q < RB / 16; ++q) {
+                const float va = Wn[(2 * (w + NW * q) + half) * LDW + jj];
+                gacc = mfma32(va, va, gacc);
+            }
+        } else {
+            // the block's share of the four tiles of W^T W: wave w takes tile w % 4 over the rows of
+            // half w / 4 of the block; the two halves meet in the (now free) totals and are added,
+            // in order, to the running tiles
+            const int ta = (w & 3) >> 1, tb = w & 1, hb = w >> 2;
+            f32x16 g2 = {0};
+#pragma unroll
+            for (int q = 0; q < RB / 4; ++q) {
+                const int row = hb * (RB / 2) + 2 * q + half;
+                g2 = mfma32(Wn[row * LDW + 32 * ta + jj], Wn[row * LDW + 32 * tb + jj], g2);
+            }
+#pragma unroll
+            for (int v = 0; v < 16; ++v) T[hb * 4096 + (w & 3) * 1024 + v * 64 + lane] = g2[v];
+            __syncthreads();
+            for (int e = tid; e < 4096; e += 64 * NW) Grun[e] += T[e] + T[4096 + e];
         }
         __syncthreads();                           // LDS goes back to the staging tiles
     }
@@ -1447,15 +1479,19 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
         __syncthreads();
         if (tid == 0) { double t = 0.0; for (int i = 0; i < NW; ++i) t += dsum[i]; dpart[blockIdx.x] = t; }
     }
-    // this workgroup's share of W^T W: the eight waves' tiles added in wave order
+    if (KT == 1) {
+        // this workgroup's share of W^T W: the eight waves' tiles added in wave order
 #pragma unroll
-    for (int v = 0; v < 16; ++v) lds[w * 1024 + v * 64 + lane] = gacc[v];
-    __syncthreads();
-    for (int e = tid; e < 1024; e += 64 * NW) {
-        float t = lds[e];
+        for (int v = 0; v < 16; ++v) lds[w * 1024 + v * 64 + lane] = gacc[v];
+        __syncthreads();
+        for (int e = tid; e < 1024; e += 64 * NW) {
+            float t = lds[e];
 #pragma unroll
-        for (int ww = 1; ww < NW; ++ww) t += lds[ww * 1024 + e];
-        gout[(int64_t)blockIdx.x * 1024 + e] = t;
+            for (int ww = 1; ww < NW; ++ww) t += lds[ww * 1024 + e];
+            gout[(int64_t)blockIdx.x * 1024 + e] = t;
+        }
+    } else {
+        for (int e = tid; e < 4096; e += 64 * NW) gout[(int64_t)blockIdx.x * 4096 + e] = Grun[e];
     }
 }
 
@@ -2198,34 +2234,35 @@ bool aht_rows_ok(const float *A, int64_t m, int64_t n, int k)
     // 32 rows of A are addressed with 32-bit byte offsets: 128 n < 2^31.  Short and wide matrices
     // leave most of the chip without a row block: they keep the other plans, unless the whole
     // problem is small enough to be latency bound anyway.
-    return k <= 32 && vec_ok(A, n) && n < ((int64_t)1 << 24) && (m >= 4096 || m * n <= ((int64_t)1 << 22));
+    return k <= 64 && vec_ok(A, n) && n < ((int64_t)1 << 24) && (m >= 4096 || m * n <= ((int64_t)1 << 22));
 }
 
-// row tiles per workgroup: 128-row blocks when they fill the chip, else 64-row blocks
-static int aht_rows_tiles(int64_t rows) { return (rows + 127) / 128 >= 192 ? 4 : 2; }
+// row tiles per workgroup: 128-row blocks when they fill the chip, else 64-row blocks; two
+// 32-factor tiles leave registers for two row tiles only
+static int aht_rows_tiles(int64_t rows, int k) { return k <= 32 && (rows + 127) / 128 >= 192 ? 4 : 2; }
 
-int aht_rows_blocks(int64_t rows)
+int aht_rows_blocks(int64_t rows, int k)
 {
-    const int64_t rb = 32 * aht_rows_tiles(rows);
+    const int64_t rb = 32 * aht_rows_tiles(rows, k);
     int64_t b = (rows + rb - 1) / rb;
     if (b > kFinMaxBlocks) b = kFinMaxBlocks;
     return (int)b;
 }
 
-template <int R>
+template <int R, int KT>
 static hipError_t aht_rows_launch(dim3 grid, hipStream_t st, const float *A, const u32x4 *ph, const float *GH, float *W,
                                   u32x4 *pw, float *gout, double *dpart, int64_t rows, int64_t n, int k, float eps,
                                   int mode, const BlockMap &bm)
 {
-    constexpr int kLdsBytes = (8 * 2048 + 4 * R * 1024) * (int)sizeof(float);
+    constexpr int kLdsBytes = (8 * 2048 + 4 * R * KT * 1024 + (KT == 2 ? 4096 : 0)) * (int)sizeof(float);
     static bool raised = false;      // more dynamic LDS than the default limit: asked for once per process
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&aht_rows_kernel<R>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(&aht_rows_kernel<R, KT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((aht_rows_kernel<R>), grid, dim3(512), kLdsBytes, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
+    hipLaunchKernelGGL((aht_rows_kernel<R, KT>), grid, dim3(512), kLdsBytes, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
     return hipGetLastError();
 }
 
@@ -2233,17 +2270,18 @@ hipError_t launch_aht_rows(const float *A, int64_t rows, int64_t n, int k, const
                            const float *GH, float *W, void *planesW, float *gout, float eps, hipStream_t st,
                            bool gram_only, const BlockMap *map, double *dpart, bool dry)
 {
-    if (k > 32 || !planesW || !gout) return hipErrorInvalidValue;
+    if (k > 64 || !planesW || !gout) return hipErrorInvalidValue;
     if (!gram_only && (!A || !planesH || !GH || !vec_ok(A, n) || n >= ((int64_t)1 << 24))) return hipErrorInvalidValue;
     BlockMap bm;
     if (map) bm = *map;
     else bm.on = 0;
-    const dim3 grid((unsigned)aht_rows_blocks(rows));
+    const dim3 grid((unsigned)aht_rows_blocks(rows, k));
     const u32x4 *ph = static_cast<const u32x4 *>(planesH);
     u32x4 *pw = static_cast<u32x4 *>(planesW);
     const int mode = gram_only ? 1 : (dry ? 2 : 0);
-    if (aht_rows_tiles(rows) == 4) return aht_rows_launch<4>(grid, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
-    return aht_rows_launch<2>(grid, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
+    if (k > 32) return aht_rows_launch<2, 2>(grid, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
+    if (aht_rows_tiles(rows, k) == 4) return aht_rows_launch<4, 1>(grid, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
+    return aht_rows_launch<2, 1>(grid, st, A, ph, GH, W, pw, gout, dpart, rows, n, k, eps, mode, bm);
 }
 
 hipError_t launch_sum_f64(const double *in, int64_t count, double *out, hipStream_t st)

@@ -110,15 +110,15 @@ int gram_w_blocks(int64_t rows);
 hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const float *H,
                            const float *GH, float *W, float eps, hipStream_t st, double *dpart = nullptr);
 int64_t aht_pass_blocks(int64_t rows);
-// The same update for k <= 32 as one streaming pass over the row-major A (coalesced loads turned
+// The same update for k <= 64 as one streaming pass over the row-major A (coalesced loads turned
 // through LDS, exact-piece products): planesH = piece planes of H^T (what launch_factor_update
 // writes for X = H), GH = H H^T (k x k).  Also written: the piece planes of the new W (planesW),
-// aht_rows_blocks(rows) tile sets of W^T W (gout) and dpart as above (aht_rows_blocks(rows)
+// aht_rows_blocks(rows, k) tile sets of W^T W (gout) and dpart as above (aht_rows_blocks(rows, k)
 // doubles).  gram_only: no pass and no update, only planesW and gout of W as it is.  dry: the
 // pass and the update without the stores to W and planesW (timing runs).  aht_rows_ok: the
 // shapes this kernel serves.
 bool aht_rows_ok(const float *A, int64_t m, int64_t n, int k);
-int aht_rows_blocks(int64_t rows);
+int aht_rows_blocks(int64_t rows, int k);
 hipError_t launch_aht_rows(const float *A, int64_t rows, int64_t n, int k, const void *planesH,
                            const float *GH, float *W, void *planesW, float *gout, float eps, hipStream_t st,
                            bool gram_only = false, const BlockMap *map = nullptr, double *dpart = nullptr,

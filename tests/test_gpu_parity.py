@@ -146,6 +146,24 @@ def test_row_plan_shapes(m, n, k, iters):
     check(Wg, Hg, Wr, Hr, TOL1 * iters)
 
 
+@pytest.mark.parametrize("m,n,k,iters", [(4100, 1028, 33, 2), (5000, 260, 64, 2), (20000, 128, 48, 2), (640, 512, 64, 3)])
+def test_row_plan_33_to_64_factors_without_room_for_a_transposed_copy(m, n, k, iters):
+    """From 33 to 64 factors the transposed copy comes first; a workspace that cannot hold it leaves
+    the run to the row plan (two 32-factor tiles per row tile, 64-row blocks)."""
+    A, W, H = case(m, n, k, 320 + k)
+    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, m, n, 0, k, 0), dtype=torch.uint8, device="cuda")
+    nmf.nmf_mu_set_workspace(buf)
+    try:
+        Ad, Wd, Hd = dev(A), dev(W), dev(H)
+        assert nmf.nmf_mu_dense_profile(Ad, m, n, k, dev(W), dev(H), 1, EPS)[6] == 2.0
+        nmf.nmf_mu_dense(Ad, m, n, k, Wd, Hd, iters, EPS)
+        Wg, Hg = host(Wd), host(Hd)
+    finally:
+        nmf.nmf_mu_set_workspace(None)
+    Wr, Hr = orc.mu_dense(A, W, H, iters, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, TOL1 * iters)
+
+
 def test_row_plan_zero_rows_and_columns():
     """All-zero rows and columns of A inside and at the edges of row blocks and column chunks."""
     A, W, H = case(4200, 520, 16, 310)
@@ -461,15 +479,16 @@ def test_ooc_monitor_argument_errors():
 def test_ooc_equals_small_plan_dense_bitwise_when_one_batch():
     """With one batch the out-of-memory path launches the same kernels as the
     resident path without the transposed copy of A (forced here by a caller
-    workspace too small for that copy)."""
-    A, W, H = case(640, 512, 48, 80)     # above 32 factors the resident path has no plan of its own
-    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, 640, 512, 0, 48, 0), dtype=torch.uint8, device="cuda")
+    workspace too small for that copy; n % 4 != 0 keeps both off the row plan)."""
+    m, n, k = 640, 510, 48
+    A, W, H = case(m, n, k, 80)
+    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, m, n, 0, k, 0), dtype=torch.uint8, device="cuda")
     nmf.nmf_mu_set_workspace(buf)
     try:
         Wg, Hg = run_dense(A, W, H, 4)
         Ah = torch.from_numpy(A).pin_memory()
         Wd, Hd = dev(W), dev(H)
-        nmf.nmf_mu_ooc(Ah, 640, 512, 48, Wd, Hd, 4, EPS, 640, 1 << 30)
+        nmf.nmf_mu_ooc(Ah, m, n, k, Wd, Hd, 4, EPS, m, 1 << 30)
         np.testing.assert_array_equal(host(Wd), Wg)
         np.testing.assert_array_equal(host(Hd), Hg)
     finally:
