@@ -11,8 +11,9 @@
  * eps is added once, to the finished denominator.  Operands and results are
  * IEEE single precision.  For k <= NMF_MU_MAX_K and 16-byte aligned A the two
  * products over A are formed on the bf16 matrix cores from exact pieces: every
- * float is cut into three bf16 values that add up to it bit for bit, all nine
- * piece products of a term are accumulated in fp32 (each is exact there), and
+ * float is cut into three bf16 values that add up to it bit for bit, the
+ * piece products of a term are accumulated in fp32 (each is exact there; the
+ * product of the two lowest pieces, below 2^-30 of the term, is left out), and
  * no matrix accumulator runs over more than 512 terms before it is added, in
  * rounded fp32, to a running total; long sums stay within 3e-7 relative of the
  * float64 result.  Unaligned A and the Gram matrices use the fp32 matrix

@@ -48,7 +48,7 @@ int nmf_csr_partition(const int64_t *rowptr, int64_t m, int32_t nparts, int64_t 
  * formed on the bf16 matrix cores from exact pieces: a float x is cut into
  * x = h + m + l, h = x with its significand truncated to 8 bits, m = x - h
  * truncated likewise, l = x - h - m (each piece is a bf16, the sum is x bit
- * for bit for |x| >= 2^-110); all nine piece products of a term are
+ * for bit for |x| >= 2^-110); the piece products of a term, all but l l, are
  * accumulated in fp32.  This call writes the pieces of X (rows x k, row-major,
  * device, k <= 64) as the kernels read them, with KP = 32 factor slots per
  * row group for k <= 32 and KP = 64 above: for row group g = row / 8, piece

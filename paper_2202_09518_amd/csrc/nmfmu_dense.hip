@@ -17,8 +17,9 @@
 //       shapes the others do not serve (unaligned A, short wide matrices)
 //   gram_kernel, gram_sum_kernel, residual_*_kernel, objective_kernel : the small rest.
 // For k <= 64 and aligned A the products are exact: fp32 operands cut into three
-// bf16 pieces each, nine piece products per term on v_mfma_f32_32x32x16_bf16 with
-// fp32 accumulation (see split3 below).  wta_pass_kernel and aht_pass_kernel use
+// bf16 pieces each, eight of the nine piece products per term (all but the lowest,
+// below 2^-30 of the term) on v_mfma_f32_32x32x16_bf16 with fp32 accumulation (see
+// split3 below).  wta_pass_kernel and aht_pass_kernel use
 // v_mfma_f32_32x32x2_f32 on the floats themselves.
 //
 // Lane layout of v_mfma_f32_32x32x2_f32 (64 lanes, D = A_op B_op + C):
@@ -48,6 +49,9 @@ __device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c)
 // v_mfma_f32_32x32x16_bf16 on pieces computes the same sums of products as
 // v_mfma_f32_32x32x2_f32 on the floats, with the roundings of the running sums
 // only, at a quarter of the matrix-core time per product.
+// The kernels issue eight of the nine: l_x l_y is below 2^-30 |x y| (each low piece is
+// below 2^-15 of its float), a 64th of the rounding of one fp32 addition, and the passes
+// are bound by the power the matrix instructions draw: leaving it out takes 4-7 % off them.
 //
 // Lane layout of v_mfma_f32_32x32x16_bf16: A_op (32 x 16): lane l holds
 // A_op[l % 32][8 (l / 32) .. 8 (l / 32) + 7]; B_op (16 x 32): lane l holds
@@ -446,7 +450,7 @@ __global__ __launch_bounds__(256) void split_planes_kernel(const float *__restri
 // (half-wave = 8 consecutive rows, the reduction depth of one instruction), loads
 // them with eight 16-byte loads per lane, cuts each element into its pieces in
 // registers and reads the pieces of W ready-made (planes, 3 x 16 bytes per lane
-// and step).  Per column tile the nine piece products are accumulated smallest
+// and step).  Per column tile the eight piece products are accumulated smallest
 // first.  r0 of every split is a multiple of 16 (rps is), so a half-wave's rows
 // are one 8-row group of the planes.  Two waves per SIMD (256 registers each).
 // ---------------------------------------------------------------------------
@@ -509,8 +513,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_kernel(
                 at[1][pr] = pack2(m0, m1);
                 at[2][pr] = pack2(l0, l1);
             }
-            acc[q] = mfma_bf16(cur.wt[2], at[2], acc[q]);
-            acc[q] = mfma_bf16(cur.wt[2], at[1], acc[q]);
+            acc[q] = mfma_bf16(cur.wt[2], at[1], acc[q]);      // eight products, smallest first (no l l)
             acc[q] = mfma_bf16(cur.wt[1], at[2], acc[q]);
             acc[q] = mfma_bf16(cur.wt[2], at[0], acc[q]);
             acc[q] = mfma_bf16(cur.wt[1], at[1], acc[q]);
@@ -607,8 +610,7 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split_buf_kernel(
                 at[1][pr] = pack2(m0, m1);
                 at[2][pr] = pack2(l0, l1);
             }
-            acc[q] = mfma_bf16(c.wt[2], at[2], acc[q]);
-            acc[q] = mfma_bf16(c.wt[2], at[1], acc[q]);
+            acc[q] = mfma_bf16(c.wt[2], at[1], acc[q]);      // eight products, smallest first (no l l)
             acc[q] = mfma_bf16(c.wt[1], at[2], acc[q]);
             acc[q] = mfma_bf16(c.wt[2], at[0], acc[q]);
             acc[q] = mfma_bf16(c.wt[1], at[1], acc[q]);
@@ -758,9 +760,9 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kerne
                 at[1][pr] = pack2(m0, m1);
                 at[2][pr] = pack2(l0, l1);
             }
-            constexpr int PW[9] = {2, 2, 1, 2, 1, 0, 1, 0, 0}, PA[9] = {2, 1, 2, 0, 1, 2, 0, 1, 0};   // smallest first
+            constexpr int PW[8] = {2, 1, 2, 1, 0, 1, 0, 0}, PA[8] = {1, 2, 0, 1, 2, 0, 1, 0};   // smallest first, no l l
 #pragma unroll
-            for (int e = 0; e < 9; ++e)
+            for (int e = 0; e < 8; ++e)
 #pragma unroll
                 for (int t = 0; t < 2; ++t) acc[t][q] = mfma_bf16(c.wt[t][PW[e]], at[PA[e]], acc[t][q]);
         }
@@ -1323,10 +1325,10 @@ __global__ __launch_bounds__(512, 2) void aht_rows_kernel(
                     at[0][2] = pack2(h0, h1), at[1][2] = pack2(m0, m1), at[2][2] = pack2(l0, l1);
                     split3(x1.z, h0, m0, l0); split3(x1.w, h1, m1, l1);
                     at[0][3] = pack2(h0, h1), at[1][3] = pack2(m0, m1), at[2][3] = pack2(l0, l1);
-                    // the nine piece products, smallest first (per 32-factor tile: independent chains)
-                    constexpr int PA[9] = {2, 2, 1, 2, 1, 0, 1, 0, 0}, PB[9] = {2, 1, 2, 0, 1, 2, 0, 1, 0};
+                    // eight piece products (no l l), smallest first (per 32-factor tile: independent chains)
+                    constexpr int PA[8] = {2, 1, 2, 1, 0, 1, 0, 0}, PB[8] = {1, 2, 0, 1, 2, 0, 1, 0};
 #pragma unroll
-                    for (int e = 0; e < 9; ++e)
+                    for (int e = 0; e < 8; ++e)
 #pragma unroll
                         for (int ft = 0; ft < KT; ++ft) a[ft] = mfma_bf16(at[PA[e]], bp[s][PB[e]][ft], a[ft]);
                 }
@@ -1601,7 +1603,7 @@ __global__ __launch_bounds__(256) void residual_kernel(const float *__restrict__
 // owns 64 of the columns and walks down all the rows of the split, a lane 2 consecutive
 // columns.  Once per wave its slab of H is cut into bf16 pieces (B_op: lane l holds factors
 // 8 (l / 32) .. + 7 of 16 for column l % 32), kept in registers for every row tile.  Per
-// 32-row tile a wave forms the two 32 x 32 tiles of W H with 2 x 9 instructions each from
+// 32-row tile a wave forms the two 32 x 32 tiles of W H with 2 x 8 instructions each from
 // pieces of the rows of W (A_op: lane l holds 8 consecutive factors of row l % 32) that the
 // workgroup makes once for its four waves (wave w cuts tile w of every group of
 // four tiles into LDS, double buffered, one barrier per group), and subtracts them from the
@@ -1705,7 +1707,7 @@ __global__ __launch_bounds__(256, 2) void residual_stream_kernel(const float *__
         }
     };
     // one tile, its A already requested: pieces of W from LDS, products, differences.  The two
-    // 32-column halves are two chains of 9 KSTEPS instructions one after the other, so the
+    // 32-column halves are two chains of 8 KSTEPS instructions one after the other, so the
     // differences of the first half can issue under the products of the second.
     auto tile = [&](const ATile &a, int buf, int t, bool valid) {
         u32x4 wp[KSTEPS][3];
@@ -1716,11 +1718,11 @@ __global__ __launch_bounds__(256, 2) void residual_stream_kernel(const float *__
         f32x16 acc[2];
         acc[0] = f32x16{0};
         acc[1] = f32x16{0};
-        constexpr int PW[9] = {2, 2, 1, 2, 1, 0, 1, 0, 0}, PH[9] = {2, 1, 2, 0, 1, 2, 0, 1, 0};   // smallest first
+        constexpr int PW[8] = {2, 1, 2, 1, 0, 1, 0, 0}, PH[8] = {1, 2, 0, 1, 2, 0, 1, 0};   // smallest first, no l l
 #pragma unroll
         for (int q = 0; q < 2; ++q)
 #pragma unroll
-            for (int e = 0; e < 9; ++e)
+            for (int e = 0; e < 8; ++e)
 #pragma unroll
                 for (int s = 0; s < KSTEPS; ++s) acc[q] = mfma_bf16(wp[s][PW[e]], hp[s][q][PH[e]], acc[q]);
         float local = 0.f;      // 32 terms per lane in fp32, double across tiles

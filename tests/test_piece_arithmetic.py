@@ -69,3 +69,19 @@ def test_nine_piece_products_are_exact_in_float32_and_sum_to_the_product():
                     assert Fraction(float(np.float32(float(prod)))) == prod
                 total += prod
         assert total == Fraction(float(x[i])) * Fraction(float(y[i]))
+
+
+def test_the_product_of_the_two_lowest_pieces_is_below_2_to_minus_30_of_the_term():
+    """The kernels leave l_x l_y out: each lowest piece is below 2^-15 of its float (h keeps 8
+    significant bits, m the next 8 from the remainder's leading bit on), so the eight products
+    they keep give x y to 2^-30, a 64th of one float32 rounding."""
+    x, y = sample(2000, 5), sample(2000, 6)
+    px, py = pieces(x), pieces(y)
+    for i in range(x.size):
+        exact = Fraction(float(x[i])) * Fraction(float(y[i]))
+        assert abs(Fraction(float(px[2][i]))) * 2 ** 15 <= abs(Fraction(float(x[i])))
+        dropped = Fraction(float(px[2][i])) * Fraction(float(py[2][i]))
+        assert abs(dropped) * 2 ** 30 <= abs(exact)
+        kept = sum(Fraction(float(a[i])) * Fraction(float(b[i]))
+                   for ia, a in enumerate(px) for ib, b in enumerate(py) if (ia, ib) != (2, 2))
+        assert kept + dropped == exact
