@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, published
 # HBM bytes per launch of the two streaming pass kernels on the default workload (row plan), from
 # the FETCH_SIZE / WRITE_SIZE counters in profiles/dense_c2_hbm_traffic_pmc.txt (scaled by the
 # plain-copy calibration stated there); only reported when that workload is the one timed.
-C2_PASS_TRAFFIC_BYTES = {"wta_pass": (1073360.9 * 2.0 + 8208.6) * 1024.0, "aht_pass": (1101514.4 * 2.0 + 4437.3) * 1024.0}
+C2_PASS_TRAFFIC_BYTES = {"wta_pass": (1073365.2 * 2.0 + 8208.6) * 1024.0, "aht_pass": (1112235.3 * 2.0 + 4437.3) * 1024.0}
 # HBM bytes per iteration of the sparse workload c3 (both gather launches), from the counters in
 # profiles/csr_c3_hbm_traffic_pmc.txt (scaled by the plain-copy calibration stated there).
 C3_ITERATION_TRAFFIC_BYTES = (30746040.6 + 30666910.4) * 2.0 * 1024.0 + (131072.0 + 524328.3) * 1024.0
@@ -423,10 +423,10 @@ def bench_c5(args, torch, nmf, nmf_inputs):
            "config": {"workload": f"c5: dense {m}x{n}, {copies} perturbed copies x k={kmin}..{kmax} = {nruns} runs; "
                                   f"timed {iters} iterations per run, scaled to 500"},
            "tflops_useful_fp32": useful / (t1 - t0) / 1e12,
-           # matrix-core bound: every fp32 product is nine bf16 piece products, so the instructions issued
-           # amount to 9 x the useful operations (stacks are padded to 32 or 64 factors on top of that)
-           "roofline": {"bound": "mfma", "achieved": 9 * useful / (t1 - t0) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
-                        "frac": 9 * useful / (t1 - t0) / 1e12 / 2500.0, "traffic": None, "instruction": "bf16"}}
+           # matrix-core bound: every fp32 product is eight bf16 piece products, so the instructions issued
+           # amount to 8 x the useful operations (stacks are padded to 32 or 64 factors on top of that)
+           "roofline": {"bound": "mfma", "achieved": 8 * useful / (t1 - t0) / 1e12, "peak": 2500.0, "unit": "TFLOP/s",
+                        "frac": 8 * useful / (t1 - t0) / 1e12 / 2500.0, "traffic": None, "instruction": "bf16"}}
     if not args.no_cpu_baseline:
         from oracle import nmf_oracle as orc
         Ah = As[0].cpu().numpy()
@@ -479,7 +479,7 @@ def main():
         import copy
         import gc
         out["sub_results"] = {}
-        for name, steps, warm in (("c1", 200, 20), ("c3", 10, 1), ("c4", 3, 0), ("c5", 10, 1)):
+        for name, steps, warm in (("c1", 200, 20), ("c3", 10, 1), ("c4", 3, 0), ("c5", 50, 1)):
             gc.collect()
             torch.cuda.synchronize()
             nmf.nmf_mu_release()
