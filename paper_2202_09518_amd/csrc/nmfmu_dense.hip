@@ -845,8 +845,9 @@ __global__ __launch_bounds__(64 * kWtaWaves, 2) void wta_pass_split64_wide_kerne
 // accumulator layout (gin), which every block sums in block order while
 // staging G into LDS.  Optional outputs: Xt (len x k), staged through LDS so a
 // block stores one contiguous run of 64 k floats, and gout: this block's
-// partial Gram tiles of the NEW X (X X^T), computed from the LDS copy with the
-// same register as both MFMA operands; the next finisher consumes them, so no
+// partial Gram tiles of the NEW X (X X^T), computed from the LDS copy (one tile: the
+// same register as both MFMA operands; four tiles at 33 to 64 factors: each wave one
+// tile over half of a chunk's columns); the next finisher consumes them, so no
 // separate Gram kernel and no cross-block reduction are needed.  With
 // part == nullptr (and splits == 0) nothing is updated and only gout is produced.
 // ---------------------------------------------------------------------------
@@ -872,38 +873,56 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int kt = (k + 31) >> 5;
 
-    for (int e = tid; e < KP * KP; e += 64 * NW) {
-        const int c = e / KP, d = e % KP;
-        float v = 0.f;
-        // Stacked independent runs: factor indices of different runs do not interact.
-        if (c < k && d < k && (!bm.on || bm.id[c] == bm.id[d])) {
-            if (Gfull) {
-                v = Gfull[c * k + d];
-            } else {
-                const int r1 = c & 31, r2 = d & 31;
-                const int pos = ((r1 & 3) + 4 * (r1 >> 3)) * 64 + r2 + 32 * ((r1 >> 2) & 1);
-                const float *src = gin + (int64_t)((c >> 5) * kt + (d >> 5)) * 1024 + pos;
-                const int64_t stride = (int64_t)kt * kt * 1024;
-                int b = 0;
-                for (; b + 8 <= nbin; b += 8) {
-                    float t[8];
+    // A thread's entries of G (8 at KP = 64) are independent: the loads of up to four entries are
+    // requested together, kGramGroup sets per entry at a time (each trip to L2 costs a microsecond
+    // here), and each entry's sets are added in set order.
+    constexpr int EPT = (KP * KP + 64 * NW - 1) / (64 * NW), EG = EPT < 4 ? EPT : 4;
+    for (int i0 = 0; i0 < EPT; i0 += EG) {
+        float gv[EG];
+        const float *src[EG];
+        bool use[EG];
+        const int64_t stride = (int64_t)kt * kt * 1024;
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) t[u] = src[(b + u) * stride];
+        for (int i = 0; i < EG; ++i) {
+            const int e = tid + 64 * NW * (i0 + i);
+            const int c = e / KP, d = e % KP;
+            // Stacked independent runs: factor indices of different runs do not interact.
+            use[i] = e < KP * KP && c < k && d < k && (!bm.on || bm.id[c] == bm.id[d]);
+            const int r1 = c & 31, r2 = d & 31;
+            const int pos = ((r1 & 3) + 4 * (r1 >> 3)) * 64 + r2 + 32 * ((r1 >> 2) & 1);
+            src[i] = Gfull ? Gfull + (use[i] ? c * k + d : 0)
+                           : gin + (use[i] ? (int64_t)((c >> 5) * kt + (d >> 5)) * 1024 + pos : 0);
+            gv[i] = 0.f;
+        }
+        if (Gfull) {
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) v += t[u];
-                }
-                for (; b < nbin; ++b) v += src[b * stride];
+            for (int i = 0; i < EG; ++i) gv[i] = *src[i];
+        } else {
+            for (int b = 0; b < nbin; b += kGramGroup) {
+                float t[EG][kGramGroup];
+#pragma unroll
+                for (int i = 0; i < EG; ++i)
+#pragma unroll
+                    for (int u = 0; u < kGramGroup; ++u) t[i][u] = src[i][(b + u < nbin ? b + u : 0) * stride];
+#pragma unroll
+                for (int i = 0; i < EG; ++i)
+#pragma unroll
+                    for (int u = 0; u < kGramGroup; ++u) gv[i] += b + u < nbin ? t[i][u] : 0.f;
             }
         }
-        Gs[c * LD + d] = v;
+#pragma unroll
+        for (int i = 0; i < EG; ++i) {
+            const int e = tid + 64 * NW * (i0 + i);
+            if (e < KP * KP) Gs[(e / KP) * LD + e % KP] = use[i] ? gv[i] : 0.f;
+        }
     }
     __syncthreads();
 
-    f32x16 acc[KT][KT];
-#pragma unroll
-    for (int a = 0; a < KT; ++a)
-#pragma unroll
-        for (int b = 0; b < KT; ++b) acc[a][b] = f32x16{0};
+    // Gram tiles of the new X.  One tile (KT = 1): every wave adds up its share of the columns.
+    // Four tiles (KT = 2): wave w adds up tile w % 4 over half w / 4 of a chunk's columns, which
+    // leaves one accumulator per wave and one round through LDS at the end instead of four.
+    constexpr bool G2 = KT == 2;
+    f32x16 acc = {0};
 
     const int jl = lane, grp = w;
     double dacc = 0.0;   // sum over this thread's entries of numerator x new value (objective monitor)
@@ -1009,20 +1028,21 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
                 for (int pl = 0; pl < 3; ++pl) planes[(grow * 3 + pl) * PKP + c] = o[pl];
             }
         }
-        if (gout) {
+        if (gout && G2) {
+            const int jj = lane & 31, half = lane >> 5;
+            const int ta = (w & 3) >> 1, tb = w & 1, hb = w >> 2;
+#pragma unroll
+            for (int q = 0; q < 16; ++q) {
+                const int row = 32 * hb + 2 * q + half;    // column pair of this chunk
+                acc = mfma32(Ts[row * LDT + 32 * ta + jj], Ts[row * LDT + 32 * tb + jj], acc);
+            }
+        } else if (gout) {
             const int jj = lane & 31, half = lane >> 5;
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
                 const int row = 2 * (w + NW * q) + half;   // column pair of this chunk
-#pragma unroll
-                for (int a = 0; a < KT; ++a) {
-                    const float va = Ts[row * LDT + 32 * a + jj];
-#pragma unroll
-                    for (int b = 0; b < KT; ++b) {
-                        const float vb = Ts[row * LDT + 32 * b + jj];
-                        acc[a][b] = mfma32(va, vb, acc[a][b]);
-                    }
-                }
+                const float va = Ts[row * LDT + jj];
+                acc = mfma32(va, va, acc);
             }
         }
     }
@@ -1042,22 +1062,25 @@ __global__ __launch_bounds__(512) void factor_update_kernel(float *X, float *Xt,
     __syncthreads();   // the last chunk's readers of Ts are done: Sm changes hands
     // Rows and columns of a tile at factor indices >= k hold whatever LDS held;
     // consumers never read them.
-    for (int a = 0; a < KT; ++a)
-        for (int b = 0; b < KT; ++b) {
-            if (a >= kt || b >= kt) continue;
-            // every wave parks its tile, then all threads add the eight copies in wave order
+    // every wave parks its tile, then all threads add the copies in wave order: the two halves
+    // of each of four tiles, or the eight shares of the one tile
 #pragma unroll
-            for (int v = 0; v < 16; ++v) Sm[w * 1024 + v * 64 + lane] = acc[a][b][v];
-            __syncthreads();
-            float *dst = gout + ((int64_t)blockIdx.x * kt * kt + a * kt + b) * 1024;
-            for (int e = tid; e < 1024; e += 64 * NW) {
-                float t = Sm[e];
-#pragma unroll
-                for (int ww = 1; ww < NW; ++ww) t += Sm[ww * 1024 + e];
-                dst[e] = t;
-            }
-            __syncthreads();
+    for (int v = 0; v < 16; ++v) Sm[w * 1024 + v * 64 + lane] = acc[v];
+    __syncthreads();
+    if (G2) {
+        for (int e = tid; e < 4096; e += 64 * NW) {
+            const int a = e >> 11, b = (e >> 10) & 1;
+            if (a < kt && b < kt) gout[((int64_t)blockIdx.x * kt * kt + a * kt + b) * 1024 + (e & 1023)] = Sm[e] + Sm[4096 + e];
         }
+    } else {
+        float *dst = gout + (int64_t)blockIdx.x * 1024;
+        for (int e = tid; e < 1024; e += 64 * NW) {
+            float t = Sm[e];
+#pragma unroll
+            for (int ww = 1; ww < NW; ++ww) t += Sm[ww * 1024 + e];
+            dst[e] = t;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
