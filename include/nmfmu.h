@@ -93,7 +93,11 @@ const char *nmf_last_error(void);
  * workspace kind 0.  Without room for that copy: the row plan for
  * 33 <= k <= 64 where it applies (its A H^T pass is about a fifth slower than
  * the mirrored one), else the small plan, a direct A H^T kernel on A (lanes
- * down the rows: slower); workspace kind 4.
+ * down the rows: slower); workspace kind 4.  An A whose base is not 16-byte
+ * aligned or whose n is not a multiple of 4 is copied once per call, with H,
+ * into aligned arrays of n rounded up to 4 columns (zero columns change no
+ * result) when the workspace can hold them (about the size of kind 0) and eps
+ * is a normal positive float, and the row plan runs on the copies.
  * Ranks NMF_MU_MAX_K < k <= NMF_MU_MAX_K_SLICED run the same iteration with every
  * product written as F^T X (a reduction over the rows of two row-major
  * matrices) and computed 64 factor columns of F at a time by the k <= 64 pass

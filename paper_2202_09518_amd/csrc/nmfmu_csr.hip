@@ -387,6 +387,32 @@ __global__ __launch_bounds__(256) void fill_i64_kernel(int64_t *p, int64_t count
         p[i] = v;
 }
 
+// dst (rows x ld_dst) = the first `cols` columns of src (rows x ld_src), columns cols .. ld_dst - 1
+// of dst set to zero (cols <= ld_dst).  One workgroup per row at a time; a wave instruction moves
+// 64 consecutive floats, eight per thread in flight.  No alignment is asked of either side.
+__global__ __launch_bounds__(256) void pad_copy_kernel(const float *__restrict__ src, int64_t ld_src,
+                                                       float *__restrict__ dst, int64_t ld_dst, int64_t rows,
+                                                       int64_t cols)
+{
+    for (int64_t r = blockIdx.x; r < rows; r += gridDim.x) {
+        const float *s = src + r * ld_src;
+        float *d = dst + r * ld_dst;
+        for (int64_t c0 = threadIdx.x; c0 < ld_dst; c0 += 2048) {
+            float v[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int64_t c = c0 + 256 * q;
+                v[q] = c < cols ? s[c] : 0.f;
+            }
+#pragma unroll
+            for (int q = 0; q < 8; ++q) {
+                const int64_t c = c0 + 256 * q;
+                if (c < ld_dst) d[c] = v[q];
+            }
+        }
+    }
+}
+
 // out (cols x rows) = in^T, in is rows x cols.
 __global__ __launch_bounds__(256) void transpose_kernel(const float *__restrict__ in, int64_t rows,
                                                         int64_t cols, float *__restrict__ out)
@@ -485,6 +511,15 @@ hipError_t launch_fill_f32(float *p, int64_t count, float v, hipStream_t st)
     if (b > 8192) b = 8192;
     if (b < 1) b = 1;
     hipLaunchKernelGGL(fill_f32_kernel, dim3((unsigned)b), dim3(256), 0, st, p, count, v);
+    return hipGetLastError();
+}
+
+hipError_t launch_pad_copy(const float *src, int64_t ld_src, float *dst, int64_t ld_dst, int64_t rows, int64_t cols,
+                           hipStream_t st)
+{
+    if (cols > ld_dst || cols > ld_src) return hipErrorInvalidValue;
+    const int64_t b = rows < 8192 ? rows : 8192;
+    hipLaunchKernelGGL(pad_copy_kernel, dim3((unsigned)(b < 1 ? 1 : b)), dim3(256), 0, st, src, ld_src, dst, ld_dst, rows, cols);
     return hipGetLastError();
 }
 

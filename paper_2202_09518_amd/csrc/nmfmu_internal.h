@@ -176,6 +176,10 @@ hipError_t launch_csc_build(const int64_t *rowptr, const int32_t *colidx, const 
 // dup_part (csc_finish_blocks(nnz) doubles, at least one): their sum is what repeated (row, column)
 // pairs add to the squared Frobenius norm of the matrix beyond the sum of the squared stored values.
 int csc_finish_blocks(int64_t nnz);
+// dst (rows x ld_dst) = the first `cols` columns of src (rows x ld_src); the columns of dst from
+// `cols` on are set to zero.  Any alignment.
+hipError_t launch_pad_copy(const float *src, int64_t ld_src, float *dst, int64_t ld_dst, int64_t rows, int64_t cols,
+                           hipStream_t st);
 // out (cols x rows) = in^T.
 hipError_t launch_transpose(const float *in, int64_t rows, int64_t cols, float *out, hipStream_t st);
 

@@ -164,6 +164,28 @@ def test_row_plan_33_to_64_factors_without_room_for_a_transposed_copy(m, n, k, i
     check(Wg, Hg, Wr, Hr, TOL1 * iters)
 
 
+@pytest.mark.parametrize("m,n,k,off,iters", [(5000, 1031, 32, 0, 2), (4100, 1028, 17, 1, 2), (6000, 514, 48, 3, 2),
+                                             (300, 203, 8, 2, 3), (4097, 5, 3, 0, 2)])
+def test_misaligned_a_runs_on_an_aligned_padded_copy(m, n, k, off, iters):
+    """n % 4 != 0 or a base that is not 16-byte aligned: the call copies A and H into aligned arrays
+    with zero columns appended and runs the row plan there; H comes back without the padding."""
+    A, W, H = case(m, n, k, 330 + k)
+    buf = torch.zeros(m * n + 8, dtype=torch.float32, device="cuda")
+    Ad = buf[off:off + m * n].view(m, n)
+    Ad.copy_(dev(A))
+    hbuf = torch.full((k * n + 8,), -7.0, dtype=torch.float32, device="cuda")
+    Hd = hbuf[off:off + k * n].view(k, n)
+    Hd.copy_(dev(H))
+    Wd = dev(W)
+    nmf.nmf_mu_dense(Ad, m, n, k, Wd, Hd, iters, EPS)
+    Wg, Hg = host(Wd), host(Hd)
+    Wr, Hr = orc.mu_dense(A, W, H, iters, float(np.float32(EPS)))
+    check(Wg, Hg, Wr, Hr, TOL1 * iters)
+    torch.cuda.synchronize()
+    guard = hbuf.cpu().numpy()
+    assert (guard[:off] == -7.0).all() and (guard[off + k * n:] == -7.0).all()     # nothing written around H
+
+
 def test_row_plan_zero_rows_and_columns():
     """All-zero rows and columns of A inside and at the edges of row blocks and column chunks."""
     A, W, H = case(4200, 520, 16, 310)
