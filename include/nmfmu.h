@@ -85,7 +85,7 @@ const char *nmf_last_error(void);
  *   iters  >= 0;  eps >= 0 and finite
  * Asynchronous on `stream`.  Three plans, chosen per call; they give the same
  * iteration and differ in low-order bits.  Row plan (16-byte aligned A,
- * n % 4 == 0, n < 2^24, and m >= 4096 or m n <= 2^22): both products stream
+ * n % 4 == 0, n < 2^24, and m >= 12288 with n >= 512, or m n <= 2^22): both products stream
  * the row-major A, the W update is fused into the A H^T pass; workspace kind 4.
  * It comes first for k <= 32.  Mirrored plan (33 <= k <= 64, and shapes the
  * row plan does not serve, if the workspace can hold a second copy of A): A is

@@ -189,7 +189,8 @@ DensePlan carve_dense(void *ws, int64_t m, int64_t n, int k, bool mirrored)
 static bool rows_plan_first(const float *A, int64_t m, int64_t n, int k) { return k <= 32 && aht_rows_ok(A, m, n, k); }
 static bool rows_plan_runs(const float *A, int64_t m, int64_t n, int k, bool mirrored)
 {
-    return aht_rows_ok(A, m, n, k) && (k <= 32 || !mirrored);
+    // without a transposed copy the row kernel beats the direct one on every shape it can take
+    return aht_rows_can(A, n, k) && (!mirrored || rows_plan_first(A, m, n, k));
 }
 
 // Workspace for a dense run: the mirrored plan if it can be had, else the small one.
@@ -981,7 +982,7 @@ static int ooc_run(const float *A_host, int64_t m, int64_t n, int32_t k, float *
     // batch and its scratch, ||A||^2, one objective value per iteration
     // The W update of a batch: the streaming row kernel where it applies (staging slots are aligned,
     // so that is a matter of n, k and the batch height), else the direct kernel.
-    const bool use_rows = aht_rows_ok(nullptr, batch_rows, n, k);
+    const bool use_rows = aht_rows_can(nullptr, n, k);
     auto w_blocks = [&](int64_t rows) { return use_rows ? (int64_t)aht_rows_blocks(rows, k) : aht_pass_blocks(rows); };
     const int64_t bpb = w_blocks(batch_rows);
     const size_t mon_bytes = objective_host

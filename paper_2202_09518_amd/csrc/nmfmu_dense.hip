@@ -1922,7 +1922,11 @@ int wta_splits(int64_t rows, int64_t n, int k)
         max_by_rows = fine < want ? fine : want;
     }
     if (s > max_by_rows) s = max_by_rows;
-    if (s > 32) s = 32;
+    // every split is a k x n partial that the finisher reads again, a few splits per trip to L2:
+    // 32 at most, but up to 128 while there are fewer than 16 column slabs (1048576 x 256: the pass
+    // ran on 64 workgroups)
+    const int64_t cap = slabs >= 16 ? 32 : 128;
+    if (s > cap) s = cap;
     if (s < 1) s = 1;
     return (int)s;
 }
@@ -2254,12 +2258,19 @@ hipError_t launch_aht_pass(const float *A, int64_t rows, int64_t n, int k, const
     return hipGetLastError();
 }
 
+bool aht_rows_can(const float *A, int64_t n, int k)
+{
+    // 32 rows of A are addressed with 32-bit byte offsets: 128 n < 2^31
+    return k <= 64 && vec_ok(A, n) && n < ((int64_t)1 << 24);
+}
+
 bool aht_rows_ok(const float *A, int64_t m, int64_t n, int k)
 {
-    // 32 rows of A are addressed with 32-bit byte offsets: 128 n < 2^31.  Short and wide matrices
-    // leave most of the chip without a row block: they keep the other plans, unless the whole
-    // problem is small enough to be latency bound anyway.
-    return k <= 64 && vec_ok(A, n) && n < ((int64_t)1 << 24) && (m >= 4096 || m * n <= ((int64_t)1 << 22));
+    // Short and wide matrices leave most of the chip without a row block (64-row blocks: 12288 rows
+    // are 192 of them), and with fewer than eight 64-column chunks some of a workgroup's waves have
+    // none: such shapes do better on a transposed copy, unless the whole problem is small enough to be
+    // latency bound anyway.
+    return aht_rows_can(A, n, k) && ((m >= 12288 && n >= 512) || m * n <= ((int64_t)1 << 22));
 }
 
 // row tiles per workgroup: 128-row blocks when they fill the chip, else 64-row blocks; two

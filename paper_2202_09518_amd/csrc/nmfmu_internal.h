@@ -115,8 +115,9 @@ int64_t aht_pass_blocks(int64_t rows);
 // writes for X = H), GH = H H^T (k x k).  Also written: the piece planes of the new W (planesW),
 // aht_rows_blocks(rows, k) tile sets of W^T W (gout) and dpart as above (aht_rows_blocks(rows, k)
 // doubles).  gram_only: no pass and no update, only planesW and gout of W as it is.  dry: the
-// pass and the update without the stores to W and planesW (timing runs).  aht_rows_ok: the
-// shapes this kernel serves.
+// pass and the update without the stores to W and planesW (timing runs).  aht_rows_can: the
+// operands this kernel takes; aht_rows_ok: and a shape on which it fills the chip.
+bool aht_rows_can(const float *A, int64_t n, int k);
 bool aht_rows_ok(const float *A, int64_t m, int64_t n, int k);
 int aht_rows_blocks(int64_t rows, int k);
 hipError_t launch_aht_rows(const float *A, int64_t rows, int64_t n, int k, const void *planesH,

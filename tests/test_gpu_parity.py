@@ -134,15 +134,27 @@ def test_mu_dense_one_iteration(m, n, k):
 
 # The row plan (k <= 32, m >= 4096 or a small problem): ragged rows and columns, more row blocks
 # than workgroups (the kernel then walks several blocks), 64-row and 128-row blocks, ranks off the
-# tile sizes.  k = 33 and a misaligned view take the other plans on the same shapes.
+# tile sizes.
 @pytest.mark.parametrize("m,n,k,iters", [
     (4100, 1028, 17, 2), (5000, 260, 32, 2), (40000, 128, 8, 2), (4097, 68, 1, 1), (33000, 1200, 32, 1),
     (24600, 4, 3, 2), (8192, 8256, 32, 1), (4100, 1028, 33, 1),
 ])
 def test_row_plan_shapes(m, n, k, iters):
+    """Run twice: as the library plans it (the row plan for 12288 rows and 512 columns or more and for
+    small problems, a transposed copy otherwise), and with a workspace that has no room for a copy,
+    which leaves every one of these shapes to the row kernel."""
     A, W, H = case(m, n, k, 300 + k)
-    Wg, Hg = run_dense(A, W, H, iters)
     Wr, Hr = orc.mu_dense(A, W, H, iters, float(np.float32(EPS)))
+    Wg, Hg = run_dense(A, W, H, iters)
+    check(Wg, Hg, Wr, Hr, TOL1 * iters)
+    buf = torch.empty(nmf.nmf_mu_workspace_bytes(4, m, n, 0, k, 0), dtype=torch.uint8, device="cuda")
+    nmf.nmf_mu_set_workspace(buf)
+    try:
+        assert nmf.nmf_mu_dense_profile(dev(A), m, n, k, dev(W), dev(H), 1, EPS)[6] == 2.0
+        Wg, Hg = run_dense(A, W, H, iters)
+    finally:
+        torch.cuda.synchronize()
+        nmf.nmf_mu_set_workspace(None)
     check(Wg, Hg, Wr, Hr, TOL1 * iters)
 
 
