@@ -170,7 +170,15 @@ def test_row_plan_33_to_64_factors_without_room_for_a_transposed_copy(m, n, k, i
         assert nmf.nmf_mu_dense_profile(Ad, m, n, k, dev(W), dev(H), 1, EPS)[6] == 2.0
         nmf.nmf_mu_dense(Ad, m, n, k, Wd, Hd, iters, EPS)
         Wg, Hg = host(Wd), host(Hd)
+        # the same run cut into two calls: the seeding of W^T W and of the planes of W at call entry
+        # adds up in the order of an updating launch, so the bits are the same
+        W2, H2 = dev(W), dev(H)
+        nmf.nmf_mu_dense(Ad, m, n, k, W2, H2, 1, EPS)
+        nmf.nmf_mu_dense(Ad, m, n, k, W2, H2, iters - 1, EPS)
+        np.testing.assert_array_equal(host(W2), Wg)
+        np.testing.assert_array_equal(host(H2), Hg)
     finally:
+        torch.cuda.synchronize()
         nmf.nmf_mu_set_workspace(None)
     Wr, Hr = orc.mu_dense(A, W, H, iters, float(np.float32(EPS)))
     check(Wg, Hg, Wr, Hr, TOL1 * iters)
