@@ -479,7 +479,7 @@ def main():
         import copy
         import gc
         out["sub_results"] = {}
-        for name, steps, warm in (("c1", 200, 20), ("c3", 10, 1), ("c4", 3, 0), ("c5", 50, 1)):
+        for name, steps, warm in (("c1", 200, 20), ("c3", 25, 1), ("c4", 3, 0), ("c5", 50, 1)):
             gc.collect()
             torch.cuda.synchronize()
             nmf.nmf_mu_release()
