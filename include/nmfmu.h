@@ -262,8 +262,9 @@ int nmf_mu_ooc(const float *A_host, int64_t m, int64_t n, int32_t k,
  * of each staged batch, on the device).  Absolute error about 2e-7 ||A||^2 / f.
  * k <= NMF_MU_MAX_K.  objective_host: HOST memory, iters doubles.  Blocking.
  * W, H as nmf_mu_ooc (bit-identical result).  The workspace is
- * nmf_mu_workspace_bytes(kind 2) plus 8 bytes for each of: ceil(batch_rows / 64)
- * per batch, one per batch, 4097, and iters (each group rounded up to 256 bytes).
+ * nmf_mu_workspace_bytes(kind 2) plus 8 bytes for each of: at most
+ * ceil(batch_rows / 64) per batch, one per batch, 4097, and iters (each group
+ * rounded up to 256 bytes).
  */
 int nmf_mu_ooc_monitor(const float *A_host, int64_t m, int64_t n, int32_t k,
                        float *W, float *H, int32_t iters, float eps,
