@@ -63,6 +63,42 @@ def test_config2_full_size_1_and_100_iterations():
     assert bool((W >= 0).all()) and bool((H >= 0).all())
 
 
+def test_config2_size_misaligned_and_64_factors_without_a_transposed_copy():
+    """The two plans that stand in for the row plan of config 2 at its size: an A whose rows are
+    16382 floats long at an odd float offset (copied once into an aligned, zero-padded array), and
+    64 factors with a workspace that has no room for a transposed copy (the row kernel with two
+    32-factor tiles).  Two iterations each."""
+    m, n, k = 32768, 16382, 32
+    base = nmf_inputs.dense_planted(m, 16384, 32, seed=1002, device="cuda")
+    buf = torch.empty(m * n + 8, dtype=torch.float32, device="cuda")
+    A = buf[1:1 + m * n].view(m, n)
+    A.copy_(base[:, :n])
+    del base
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2002, device="cuda")
+    Ah, W0, H0 = A.cpu().numpy(), W.cpu().numpy(), H.cpu().numpy()
+    nmf.nmf_mu_dense(A, m, n, k, W, H, 2, EPS)
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 2, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    say(f"32768 x 16382 at a 4-byte offset, 2 iterations: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 2e-5
+    del A, buf, W, H
+    m, n, k = 32768, 16384, 64
+    A = nmf_inputs.dense_planted(m, n, 32, seed=1002, device="cuda")
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2012, device="cuda")
+    Ah, W0, H0 = A.cpu().numpy(), W.cpu().numpy(), H.cpu().numpy()
+    ws = torch.empty(nmf.nmf_mu_workspace_bytes(4, m, n, 0, k, 0), dtype=torch.uint8, device="cuda")
+    nmf.nmf_mu_set_workspace(ws)
+    try:
+        nmf.nmf_mu_dense(A, m, n, k, W, H, 2, EPS)
+        torch.cuda.synchronize()
+    finally:
+        nmf.nmf_mu_set_workspace(None)
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 2, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    say(f"32768 x 16384, k = 64 on the row kernel, 2 iterations: rel err W {ew:.2e} H {eh:.2e}")
+    assert max(ew, eh) < 2e-5
+
+
 def test_config3_full_size_one_iteration():
     m, n, k = 4194304, 1048576, 32
     rowptr, colidx, vals = nmf_inputs.csr_uniform(m, n, 1e-4, seed=1003, device="cuda")
