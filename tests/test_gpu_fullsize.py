@@ -99,6 +99,25 @@ def test_config2_size_misaligned_and_64_factors_without_a_transposed_copy():
     assert max(ew, eh) < 2e-5
 
 
+def test_streamed_batches_of_32768_rows_k32():
+    """Streamed dense run whose batches take the row kernel with four row tiles per wave (128-row
+    blocks: 24576 rows or more per batch), last batch ragged; with the objective of every iteration."""
+    m, n, k, batch = 90000, 2048, 32, 32768
+    A = nmf_inputs.dense_planted(m, n, 32, seed=1004)
+    W, H = nmf_inputs.init_factors(m, n, k, seed=2004, device="cuda")
+    W0, H0 = W.cpu().numpy(), H.cpu().numpy()
+    Ap = A.pin_memory()
+    obj = nmf.nmf_mu_ooc_monitor(Ap, m, n, k, W, H, 3, EPS, batch, 3 * batch * n * 4 + 4096)
+    Ah = A.numpy()
+    Wr, Hr = orc.mu_dense(Ah, W0, H0, 3, EPSD)
+    ew, eh = errs(W, H, Wr, Hr)
+    want = orc.residual_dense(Ah, Wr, Hr)
+    say(f"streamed 90000 x 2048, k = 32, batches of 32768 rows, 3 iterations: rel err W {ew:.2e} H {eh:.2e}; "
+        f"objective {obj[-1]:.6e} against {want:.6e}")
+    assert max(ew, eh) < 3e-5
+    assert abs(obj[-1] - want) < 1e-3 * float(np.linalg.norm(Ah.astype(np.float64)))
+
+
 def test_config3_full_size_one_iteration():
     m, n, k = 4194304, 1048576, 32
     rowptr, colidx, vals = nmf_inputs.csr_uniform(m, n, 1e-4, seed=1003, device="cuda")
